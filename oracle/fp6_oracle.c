@@ -1,0 +1,268 @@
+/*
+ * CPU oracle for the W6A16 linear layer of ZeroQuant(4+2) (arXiv 2312.08583).
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow,
+ * obviously-correct statement of what the method computes, written from the
+ * paper.  Only the test-suite, the smoke check and the benchmark's
+ * "cpu_baseline" leg may call it.  It shares no code, header, table or helper
+ * with the HIP library and knows nothing about that library's physical plane
+ * layout: it works on one 6-bit code per weight and on the *logical* 4+2 split.
+ *
+ * Every quantity that the paper defines exactly is evaluated here in exact
+ * integer arithmetic (fp16 numbers are integer multiples of 2^-24), so that no
+ * question of intermediate rounding can arise.  The linear layer itself is the
+ * plain triple loop in double precision.
+ *
+ *   value set ........ Section 4, Eq. 2 (sign, e=3 exponent bits, bias 2^(e-1)-1 = 3,
+ *                      mantissa in [0,2)); max magnitude 28 = 2^4 * 1.75; no NaN/inf
+ *                      codes (Section 4 footnote); exponent field 0 = subnormal,
+ *                      zero included (Section 5.2 footnote).
+ *   quantizer ........ Section 4, Eq. 3: W ~ S * W_fp6 with S = max|W| / 28, one S per
+ *                      row of W (coarse-grained = row-wise, Section 3 / Appendix A),
+ *                      round-to-nearest (Section 3).
+ *   4+2 split ........ Section 5.1: first 4 bits = sign + 3-bit exponent, remaining
+ *                      2 bits = mantissa.
+ *   bias shift ....... Section 5.2, Eq. 5: the same 6 bits read with exponent bias 15
+ *                      are an fp16 bit pattern (pure padding) whose value is the FP6
+ *                      value times 2^-12; the 2^12 moves into the scale.
+ *   linear ........... Section 5.2: for row-wise scales the scale multiplies the
+ *                      finished accumulation.
+ *
+ * Readings taken where the paper is silent (listed again in the design notes):
+ *   - round-to-nearest ties go to the even magnitude code (IEEE default);
+ *   - max|W|/28 and w/S are real-number quotients, rounded once;
+ *   - |w/S| > 28 (possible because S was rounded) saturates to 28;
+ *   - the sign bit of the code is the sign bit of w (tiny negatives give -0);
+ *   - S == 0 (all-zero row or quotient rounding to zero) gives magnitude code 0;
+ *   - non-finite weights are rejected (FP6 has no code for them).
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <stdlib.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define FP6O_OK 0
+#define FP6O_ERR_NONFINITE (-5)
+#define FP6O_ERR_ARG (-1)
+
+/* ------------------------------------------------------------------ fp16 */
+
+/* |h| as an integer count of 2^-24 (the fp16 subnormal quantum).  Finite h only. */
+static int64_t half_abs_units(uint16_t h)
+{
+    int e = (h >> 10) & 0x1F;
+    int64_t f = h & 0x3FF;
+    if (e == 0) return f;                    /* subnormal: f * 2^-24            */
+    return (f | 0x400) << (e - 1);           /* (1024+f) * 2^(e-15-10) / 2^-24  */
+}
+
+static int half_is_finite(uint16_t h) { return ((h >> 10) & 0x1F) != 0x1F; }
+
+/* exact fp16 -> double */
+double fp6o_half_to_double(uint16_t h)
+{
+    int e = (h >> 10) & 0x1F;
+    int f = h & 0x3FF;
+    double v;
+    if (e == 0x1F) {
+        v = f ? (0.0 / 0.0) : (1.0 / 0.0);
+    } else {
+        /* 2^-24 * integer: exact in double */
+        v = (double)half_abs_units(h) * (1.0 / 16777216.0);
+    }
+    return (h & 0x8000) ? -v : v;
+}
+
+/*
+ * Round the non-negative rational  num / (den * 2^24)  to the nearest fp16,
+ * ties to the even significand, overflow to infinity (IEEE 754
+ * roundTiesToEven).  Returns the 15 magnitude bits.  den > 0.
+ * The fp16 grid, in units of 2^-24, is { q * 2^x : 0 <= q < 2^11, x >= 0 }.
+ */
+static uint16_t round_units_to_half(int64_t num, int64_t den)
+{
+    int x = 0;
+    /* smallest x with num / (den * 2^x) < 2^11 */
+    while (x < 40 && num >= ((den << x) << 11)) x++;
+    int64_t d = den << x;
+    int64_t q = num / d, rem = num % d;
+    if (2 * rem > d || (2 * rem == d && (q & 1))) q++;
+    if (q == 2048) { q = 1024; x++; }
+    /* value = q * 2^x units of 2^-24 */
+    if (q < 1024) {
+        /* only possible for x == 0: subnormal (or zero) */
+        return (uint16_t)q;
+    }
+    int e = x + 1;                 /* biased exponent: (1024+f)*2^(e-1) units */
+    if (e >= 0x1F) return 0x7C00;  /* overflow -> inf */
+    return (uint16_t)((e << 10) | (q & 0x3FF));
+}
+
+/* RNE_fp16( num / (den * 2^24) ) for num >= 0, den > 0: the rounding helper on its
+ * own, exposed so that tests can pin it against a library's fp16 rounding. */
+uint16_t fp6o_round_ratio_to_half(int64_t num, int64_t den)
+{
+    if (num < 0 || den <= 0) return 0x7E00;
+    return round_units_to_half(num, den);
+}
+
+/* ------------------------------------------------------------------ E3M2 */
+
+/* 16 * magnitude of the 5-bit magnitude code  eee mm  (Eq. 2 with e=3, b=3):
+ *   eee == 0 : subnormal, 2^(1-3) * (mm/4)           = mm / 16
+ *   else     : normal,    2^(eee-3) * (1 + mm/4)                          */
+static int mag16(int c5)
+{
+    int e = (c5 >> 2) & 7, m = c5 & 3;
+    if (e == 0) return m;
+    return (4 + m) << (e - 1);     /* 16 * 2^(e-3) * (4+m)/4 */
+}
+
+/* value of the 6-bit code  s eee mm */
+double fp6o_e3m2_value(int code)
+{
+    double v = (double)mag16(code & 31) / 16.0;
+    return (code & 32) ? -v : v;
+}
+
+/* Eq. 5: the code's bits re-read with bias 15 are these fp16 bits
+ * (sign -> bit 15, eee -> low three exponent bits, mm -> top two mantissa bits);
+ * fp16(bits) * 2^12 == fp6o_e3m2_value(code). */
+uint16_t fp6o_bias_shift_bits(int code)
+{
+    int s = (code >> 5) & 1, e = (code >> 2) & 7, m = code & 3;
+    return (uint16_t)((s << 15) | (e << 10) | (m << 8));
+}
+
+/* ------------------------------------------------------------- quantizer */
+
+/* S = RNE_fp16( max|w| / 28 ) for one row (Eq. 3 and the line below it). */
+int fp6o_row_scale(const uint16_t *w, int64_t K, uint16_t *S)
+{
+    int64_t amax = 0;
+    for (int64_t k = 0; k < K; k++) {
+        if (!half_is_finite(w[k])) return FP6O_ERR_NONFINITE;
+        int64_t a = half_abs_units(w[k]);
+        if (a > amax) amax = a;
+    }
+    *S = round_units_to_half(amax, 28);
+    return FP6O_OK;
+}
+
+/* nearest E3M2 magnitude code to |w| / S; exact; ties -> even code */
+static int nearest_mag_code(int64_t w_units, int64_t s_units)
+{
+    if (s_units == 0) return 0;
+    int best = 0;
+    int64_t best_d = -1;
+    for (int c = 0; c < 32; c++) {
+        /* | |w|/S - mag | * 16 * S  in units of 2^-24 */
+        int64_t d = 16 * w_units - s_units * (int64_t)mag16(c);
+        if (d < 0) d = -d;
+        if (best_d < 0 || d < best_d || (d == best_d && (c & 1) == 0 && (best & 1) == 1)) {
+            best = c;
+            best_d = d;
+        }
+    }
+    return best;   /* |w|/S > 28 lands on c = 31: saturation */
+}
+
+/* W fp16 bits [N,K] row-major -> codes [N,K] (one byte each, 0..63), scales fp16 bits [N] */
+int fp6o_quantize(const uint16_t *W, int64_t N, int64_t K, uint8_t *codes, uint16_t *scales)
+{
+    if (!W || !codes || !scales || N < 0 || K < 0) return FP6O_ERR_ARG;
+    int status = FP6O_OK;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; n++) {
+        const uint16_t *w = W + n * K;
+        uint16_t S;
+        if (fp6o_row_scale(w, K, &S) != FP6O_OK) {
+#pragma omp atomic write
+            status = FP6O_ERR_NONFINITE;
+            continue;
+        }
+        scales[n] = S;
+        int64_t s_units = half_abs_units(S);
+        for (int64_t k = 0; k < K; k++) {
+            int c5 = nearest_mag_code(half_abs_units(w[k]), s_units);
+            codes[n * K + k] = (uint8_t)(((w[k] >> 15) << 5) | c5);
+        }
+    }
+    return status;
+}
+
+/* ------------------------------------------------------------- 4+2 split */
+
+/* Section 5.1: first sub-number = leading 4 bits (sign, exponent), second = last 2 (mantissa) */
+void fp6o_split42(const uint8_t *codes, int64_t count, uint8_t *hi4, uint8_t *lo2)
+{
+    for (int64_t i = 0; i < count; i++) {
+        hi4[i] = (uint8_t)((codes[i] >> 2) & 0xF);
+        lo2[i] = (uint8_t)(codes[i] & 0x3);
+    }
+}
+
+void fp6o_join42(const uint8_t *hi4, const uint8_t *lo2, int64_t count, uint8_t *codes)
+{
+    for (int64_t i = 0; i < count; i++)
+        codes[i] = (uint8_t)(((hi4[i] & 0xF) << 2) | (lo2[i] & 0x3));
+}
+
+/* ------------------------------------------------------------ dequantize */
+
+/* W_hat[n,k] = RNE_fp16( S_n * value(code) )  (Eq. 3 read right to left) */
+void fp6o_dequantize(const uint8_t *codes, const uint16_t *scales, int64_t N, int64_t K,
+                     uint16_t *W_hat)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; n++) {
+        int64_t s_units = half_abs_units(scales[n]);
+        for (int64_t k = 0; k < K; k++) {
+            int c = codes[n * K + k];
+            /* S * mag = s_units * mag16 / 16 units of 2^-24 */
+            uint16_t mag = round_units_to_half(s_units * (int64_t)mag16(c & 31), 16);
+            W_hat[n * K + k] = (uint16_t)(((c >> 5) << 15) | mag);
+        }
+    }
+}
+
+/* ---------------------------------------------------------------- linear */
+
+/* Y[m,n] = S_n * sum_k X[m,k] * value(code[n,k]), double accumulation, the scale
+ * applied to the finished sum (Section 5.2, row-wise case).  Y is [M,N] row-major. */
+void fp6o_linear(const uint16_t *X, int64_t M, const uint8_t *codes, const uint16_t *scales,
+                 int64_t N, int64_t K, double *Y)
+{
+    double *Xd = (double *)malloc(sizeof(double) * (size_t)(M * K > 0 ? M * K : 1));
+    for (int64_t i = 0; i < M * K; i++) Xd[i] = fp6o_half_to_double(X[i]);
+#pragma omp parallel
+    {
+        double *wrow = (double *)malloc(sizeof(double) * (size_t)(K > 0 ? K : 1));
+#pragma omp for schedule(static)
+        for (int64_t n = 0; n < N; n++) {
+            for (int64_t k = 0; k < K; k++) wrow[k] = fp6o_e3m2_value(codes[n * K + k]);
+            double S = fp6o_half_to_double(scales[n]);
+            for (int64_t m = 0; m < M; m++) {
+                double acc = 0.0;
+                const double *x = Xd + m * K;
+                for (int64_t k = 0; k < K; k++) acc += x[k] * wrow[k];
+                Y[m * N + n] = S * acc;
+            }
+        }
+        free(wrow);
+    }
+    free(Xd);
+}
+
+/* number of host threads the loops above use */
+int fp6o_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
