@@ -1,0 +1,162 @@
+/*
+ * fp6_linear.h - C ABI of the MI355X (gfx950) W6A16 linear layer of ZeroQuant(4+2),
+ * arXiv 2312.08583.
+ *
+ * The layer: weights are FP6 E3M2 numbers (Section 4, Eq. 2: 1 sign, 3 exponent bits
+ * with bias 3, 2 mantissa bits; largest magnitude 28; no NaN/inf; exponent field 0 is
+ * subnormal) with one fp16 scale per output channel, S = max|w| / 28 (Section 4, Eq. 3;
+ * row-wise = coarse-grained scaling, Section 3).  Each 6-bit code is stored as two
+ * sub-numbers in two separate arrays ("4+2", Section 5.1): a 4-bit one (sign + exponent)
+ * and a 2-bit one (mantissa).  At run time the two are loaded together, padded into an
+ * fp16 bit pattern without exponent arithmetic ("bias shift", Section 5.2, Eq. 5: the
+ * bits are read with exponent bias 15 and the factor 2^12 moves into the scale), and
+ * contracted with fp16 activations; the scale multiplies the finished accumulation
+ * (Section 5.2, row-wise case).
+ *
+ * Conventions
+ *   - W is [N, K] = [out_features, in_features], row-major, as in the paper's kernel
+ *     table (Appendix B: weight 5504*2048 times input 2048*8).  X is [M, K] row-major,
+ *     Y is [M, N] row-major.  There is no bias term.
+ *   - fp16 data are passed as uint16_t bit patterns.
+ *   - Every buffer pointer is a DEVICE pointer owned by the caller, 16-byte aligned.
+ *     The library never allocates, frees or synchronises; it keeps no global state.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
+ *     asynchronous on that stream.
+ *   - N and K must be positive multiples of FP6_TILE (64).  M >= 1.
+ *   - Return value: FP6_OK or a negative fp6_status.  Argument errors are found on the
+ *     host before anything is launched, so nothing is written in that case.
+ *
+ * Physical layout of the planes (layout version 1; opaque to callers, stated here so
+ * that it can be checked).  The weight is cut into tiles of 64 rows (n) by 64 columns
+ * (k); tile (nb, kb) has index ti = nb * (K/64) + kb and owns 2048 contiguous bytes of
+ * the 4-bit plane and 1024 contiguous bytes of the 2-bit plane.  Inside a tile a weight
+ * at (nn, kk) = (n % 64, k % 64) belongs to
+ *     lane      l = 16 * ((kk % 32) / 8) + (nn % 16)          (0..63, one wavefront)
+ *     fragment  f = 2 * (nn / 16) + (kk / 32)                 (0..7)
+ *     element   e = kk % 8  =  4 * grp + b   (grp = e / 4, b = e % 4)
+ *   so that one lane's eight elements of a fragment are the eight consecutive-k fp16
+ *   operands that lane feeds to v_mfma_f32_16x16x32_f16 for a 16(n) x 32(k) block.
+ *   4-bit plane: byte ti*2048 + (f/4)*1024 + l*16 + (f%4)*4 + b holds, for the two
+ *     elements b (grp 0) and 4+b (grp 1):  bit0 = sign(grp0), bit1 = sign(grp1),
+ *     bits 4..2 = exponent(grp0), bits 7..5 = exponent(grp1).
+ *   2-bit plane: byte ti*1024 + l*16 + (f/2)*4 + b holds the mantissas of elements b and
+ *     4+b of fragments f (even) and f+1: bits 1..0 = (f, grp0), 3..2 = (f, grp1),
+ *     5..4 = (f+1, grp0), 7..6 = (f+1, grp1).
+ *   A wavefront therefore fetches a whole tile with three coalesced 128-bit loads per
+ *   lane, and turns four weights at a time into the byte s00eeemm (the top byte of the
+ *   bias-15 fp16 pattern) with a handful of 32-bit logic operations.
+ */
+#ifndef FP6_LINEAR_H
+#define FP6_LINEAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FP6_TILE 64            /* N and K granularity */
+#define FP6_LAYOUT_VERSION 1
+
+typedef enum {
+    FP6_OK = 0,
+    FP6_ERR_NULL = -1,       /* a required pointer is NULL                                  */
+    FP6_ERR_SHAPE = -2,      /* M, N or K not positive, or N, K not multiples of FP6_TILE    */
+    FP6_ERR_ALIGN = -3,      /* a buffer pointer is not 16-byte aligned                      */
+    FP6_ERR_WORKSPACE = -4,  /* workspace missing or smaller than fp6_linear_workspace_bytes */
+    FP6_ERR_VARIANT = -5,    /* kernel variant / split request not valid for this shape      */
+    FP6_ERR_HIP = -6         /* the HIP runtime reported a launch error                      */
+} fp6_status;
+
+/* kernel families behind fp6_linear (see fp6_linear_variant) */
+typedef enum {
+    FP6_VARIANT_AUTO = 0,
+    FP6_VARIANT_DECODE = 1,  /* M <= 16: one MFMA row block, K split over the wavefronts of a
+                                workgroup (and optionally over workgroups), reduced on chip   */
+    FP6_VARIANT_GEMM = 2     /* any M: activations staged in LDS, wavefronts side by side in N */
+} fp6_variant;
+
+/* Layout version of the packed planes written by fp6_quantize_pack. */
+int fp6_layout_version(void);
+
+/* Human-readable text for a status code (static storage; never NULL). */
+const char *fp6_status_string(int status);
+
+/*
+ * Sizes in bytes of the three packed buffers for an [N,K] weight: N*K/2, N*K/4 (together
+ * 0.75 byte per weight, Section 5.1) and 2*N.  Host-only; any of the outputs may be NULL.
+ */
+int fp6_packed_sizes(int64_t N, int64_t K, size_t *hi_bytes, size_t *lo_bytes, size_t *scale_bytes);
+
+/*
+ * Offline step (Section 4, Eq. 3; Section 5.1; "performed statically", Section 5.2):
+ * per row n, S_n = RNE_fp16(max_k |W[n,k]| / 28); every weight is rounded to the nearest
+ * E3M2 value of W/S_n (ties to the even code, saturating at 28, sign bit kept, S_n == 0
+ * gives zero codes) and its 6 bits are split into the two planes in the layout above.
+ *   W       in   device, fp16 bits [N,K] row-major; must be finite (non-finite entries are
+ *                not detected and give unspecified codes, never a fault)
+ *   hi_plane out device, N*K/2 bytes (4-bit sub-numbers)
+ *   lo_plane out device, N*K/4 bytes (2-bit sub-numbers)
+ *   scales  out  device, fp16 bits [N]: the TRUE scale S_n (the 2^12 of the bias shift is
+ *                applied inside fp6_linear in fp32, so S need not be below 1)
+ */
+int fp6_quantize_pack(const uint16_t *W, int64_t N, int64_t K, void *hi_plane, void *lo_plane,
+                      uint16_t *scales, void *stream);
+
+/*
+ * Test utility: planes -> one code per weight, codes[n*K+k] = s<<5 | eee<<2 | mm (0..63),
+ * i.e. the logical 4-bit sub-number is codes>>2 and the 2-bit one is codes&3 (Section 5.1).
+ *   codes out device, N*K bytes
+ */
+int fp6_unpack_codes(const void *hi_plane, const void *lo_plane, int64_t N, int64_t K,
+                     uint8_t *codes, void *stream);
+
+/*
+ * Test utility: W_hat[n,k] = RNE_fp16(S_n * value(code[n,k]))  (Eq. 3 read backwards),
+ * fp16 bits [N,K] row-major, device.
+ */
+int fp6_dequantize(const void *hi_plane, const void *lo_plane, const uint16_t *scales,
+                   int64_t N, int64_t K, uint16_t *W_hat, void *stream);
+
+/*
+ * Bytes of device workspace fp6_linear may need for this shape (0 is possible).  The
+ * workspace holds fp32 partial sums of K-slices and one arrival counter per output
+ * tile.  CONTRACT: its first FP6_WORKSPACE_COUNTER_BYTES bytes must be zero before the
+ * first call that uses it; every call leaves them zero again, so one buffer can be
+ * reused by successive calls on the same stream.  Calls that share a workspace must
+ * not overlap in time.
+ */
+#define FP6_WORKSPACE_COUNTER_BYTES 16384
+size_t fp6_linear_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+/*
+ * Hot path (Sections 5.1-5.2): Y[m,n] = fp16( (sum_k X[m,k] * h(code[n,k])) * (S_n * 2^12) )
+ * where h is the code's six bits padded into an fp16 (exponent bias 15, Eq. 5), the sum
+ * is accumulated in fp32 on the matrix cores, and the row scale is applied once after
+ * the accumulation.
+ *   X         in  device, fp16 bits [M,K] row-major
+ *   hi_plane, lo_plane, scales  in  device, as written by fp6_quantize_pack
+ *   Y         out device, fp16 bits [M,N] row-major
+ *   workspace     device, >= fp6_linear_workspace_bytes(M,N,K) bytes (may be NULL if that is 0)
+ */
+int fp6_linear(const uint16_t *X, int64_t M, const void *hi_plane, const void *lo_plane,
+               const uint16_t *scales, int64_t N, int64_t K, uint16_t *Y,
+               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Same computation with the kernel family and the number of K-slices handled by separate
+ * workgroups chosen by the caller (tuning sweeps; tests that compare split and unsplit
+ * results).  variant = FP6_VARIANT_AUTO and split_k = 0 reproduce fp6_linear.
+ * split_k must divide K/64.  The workspace needed is fp6_linear_variant_workspace_bytes.
+ */
+size_t fp6_linear_variant_workspace_bytes(int64_t M, int64_t N, int64_t K, int variant, int split_k);
+int fp6_linear_variant(const uint16_t *X, int64_t M, const void *hi_plane, const void *lo_plane,
+                       const uint16_t *scales, int64_t N, int64_t K, uint16_t *Y,
+                       void *workspace, size_t workspace_bytes, void *stream,
+                       int variant, int split_k);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FP6_LINEAR_H */

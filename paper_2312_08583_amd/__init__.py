@@ -1,1 +1,7 @@
 """W6A16 FP6 (E3M2, 4+2 planes) linear layer for MI355X: Python binding of the HIP library."""
+from .binding import (  # noqa: F401
+    FP6_TILE, FP6_VARIANT_AUTO, FP6_VARIANT_DECODE, FP6_VARIANT_GEMM, Fp6Error,
+    fp6_dequantize, fp6_layout_version, fp6_linear, fp6_linear_variant,
+    fp6_linear_variant_workspace_bytes, fp6_linear_workspace_bytes, fp6_packed_sizes,
+    fp6_quantize_pack, fp6_status_string, fp6_unpack_codes, new_workspace,
+)

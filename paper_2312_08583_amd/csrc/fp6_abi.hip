@@ -1,0 +1,172 @@
+// C ABI of the library (include/fp6_linear.h): argument checks, launch planning and
+// dispatch.  Everything here runs on the host; no allocation, no synchronisation.
+#include "../../include/fp6_linear.h"
+
+#include "fp6_internal.hpp"
+
+namespace fp6 {
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static bool shape_ok(int64_t N, int64_t K)
+{
+    return N > 0 && K > 0 && N % FP6_TILE == 0 && K % FP6_TILE == 0 && N <= (int64_t)1 << 30 &&
+           K <= (int64_t)1 << 30 && N * K <= (int64_t)1 << 40;
+}
+
+// smallest divisor d of `ktiles` with units*d >= target and ktiles/d >= min_tiles; if no
+// divisor reaches the target, the largest one that keeps min_tiles per slice.
+static int pick_split(int64_t units, int64_t ktiles, int64_t target, int64_t min_tiles)
+{
+    int best = 1;
+    for (int64_t d = 1; d <= ktiles; d++) {
+        if (ktiles % d) continue;
+        if (ktiles / d < min_tiles) break;
+        best = (int)d;
+        if (units * d >= target) break;
+    }
+    return best;
+}
+
+bool make_plan(int64_t M, int64_t N, int64_t K, int variant, int split_k, LinearPlan* plan)
+{
+    const int64_t ktiles = K / FP6_TILE, nblocks = N / FP6_TILE;
+    if (variant == FP6_VARIANT_AUTO) variant = (M <= 16) ? FP6_VARIANT_DECODE : FP6_VARIANT_GEMM;
+    if (variant != FP6_VARIANT_DECODE && variant != FP6_VARIANT_GEMM) return false;
+    if (variant == FP6_VARIANT_DECODE && M > 16) return false;
+    if (split_k < 0 || (split_k > 0 && ktiles % split_k != 0)) return false;
+
+    LinearPlan p{};
+    p.variant = variant;
+    int64_t tiles, regs_per_tile;
+    if (variant == FP6_VARIANT_DECODE) {
+        p.block_m = 16;
+        p.waves = 4;
+        tiles = nblocks;
+        regs_per_tile = 256;                       // float4 per output tile (64 x 16 fp32)
+        // ~4 workgroups per compute unit, at least two tiles per wavefront
+        p.split_k = split_k ? split_k : pick_split(nblocks, ktiles, 1024, 2 * p.waves);
+    } else {
+        p.block_m = M <= 32 ? 32 : (M <= 64 ? 64 : 128);
+        p.waves = 4;
+        const int64_t mblk = (M + p.block_m - 1) / p.block_m, nblk = (nblocks + 3) / 4;
+        tiles = mblk * nblk;
+        regs_per_tile = (int64_t)(p.block_m / 16) * 4 * 256;
+        p.split_k = split_k ? split_k : pick_split(tiles, ktiles, 256, 16);
+    }
+    if (p.split_k > 1) {
+        if (tiles > kMaxCounters) {
+            if (split_k) return false;             // forced split that the counters cannot serve
+            p.split_k = 1;
+        }
+    }
+    if (p.split_k > 1) {
+        p.counters = (int)tiles;
+        p.partial_bytes = (size_t)p.split_k * (size_t)tiles * (size_t)regs_per_tile * 16u;
+    }
+    *plan = p;
+    return true;
+}
+
+static size_t plan_workspace(const LinearPlan& p) { return p.split_k > 1 ? kCounterBytes + p.partial_bytes : 0; }
+
+}  // namespace fp6
+
+using namespace fp6;
+
+extern "C" {
+
+int fp6_layout_version(void) { return FP6_LAYOUT_VERSION; }
+
+const char* fp6_status_string(int status)
+{
+    switch (status) {
+        case FP6_OK: return "ok";
+        case FP6_ERR_NULL: return "a required pointer is NULL";
+        case FP6_ERR_SHAPE: return "M, N, K must be positive and N, K multiples of 64";
+        case FP6_ERR_ALIGN: return "buffer pointers must be 16-byte aligned";
+        case FP6_ERR_WORKSPACE: return "workspace missing or too small";
+        case FP6_ERR_VARIANT: return "kernel variant or split_k not valid for this shape";
+        case FP6_ERR_HIP: return "HIP launch error";
+        default: return "unknown status";
+    }
+}
+
+int fp6_packed_sizes(int64_t N, int64_t K, size_t* hi_bytes, size_t* lo_bytes, size_t* scale_bytes)
+{
+    if (!shape_ok(N, K)) return FP6_ERR_SHAPE;
+    if (hi_bytes) *hi_bytes = (size_t)(N * K / 2);
+    if (lo_bytes) *lo_bytes = (size_t)(N * K / 4);
+    if (scale_bytes) *scale_bytes = (size_t)(2 * N);
+    return FP6_OK;
+}
+
+int fp6_quantize_pack(const uint16_t* W, int64_t N, int64_t K, void* hi_plane, void* lo_plane, uint16_t* scales,
+                      void* stream)
+{
+    if (!W || !hi_plane || !lo_plane || !scales) return FP6_ERR_NULL;
+    if (!shape_ok(N, K)) return FP6_ERR_SHAPE;
+    if (!aligned16(W) || !aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(scales)) return FP6_ERR_ALIGN;
+    return launch_quantize_pack(W, N, K, hi_plane, lo_plane, scales, (hipStream_t)stream) == hipSuccess ? FP6_OK
+                                                                                                        : FP6_ERR_HIP;
+}
+
+int fp6_unpack_codes(const void* hi_plane, const void* lo_plane, int64_t N, int64_t K, uint8_t* codes, void* stream)
+{
+    if (!hi_plane || !lo_plane || !codes) return FP6_ERR_NULL;
+    if (!shape_ok(N, K)) return FP6_ERR_SHAPE;
+    if (!aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(codes)) return FP6_ERR_ALIGN;
+    return launch_unpack_codes(hi_plane, lo_plane, N, K, codes, (hipStream_t)stream) == hipSuccess ? FP6_OK
+                                                                                                    : FP6_ERR_HIP;
+}
+
+int fp6_dequantize(const void* hi_plane, const void* lo_plane, const uint16_t* scales, int64_t N, int64_t K,
+                   uint16_t* W_hat, void* stream)
+{
+    if (!hi_plane || !lo_plane || !scales || !W_hat) return FP6_ERR_NULL;
+    if (!shape_ok(N, K)) return FP6_ERR_SHAPE;
+    if (!aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(scales) || !aligned16(W_hat)) return FP6_ERR_ALIGN;
+    return launch_dequantize(hi_plane, lo_plane, scales, N, K, W_hat, (hipStream_t)stream) == hipSuccess
+               ? FP6_OK
+               : FP6_ERR_HIP;
+}
+
+size_t fp6_linear_variant_workspace_bytes(int64_t M, int64_t N, int64_t K, int variant, int split_k)
+{
+    LinearPlan p;
+    if (M <= 0 || M > (int64_t)1 << 24 || !shape_ok(N, K) || !make_plan(M, N, K, variant, split_k, &p)) return 0;
+    return plan_workspace(p);
+}
+
+size_t fp6_linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    return fp6_linear_variant_workspace_bytes(M, N, K, FP6_VARIANT_AUTO, 0);
+}
+
+int fp6_linear_variant(const uint16_t* X, int64_t M, const void* hi_plane, const void* lo_plane,
+                       const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
+                       size_t workspace_bytes, void* stream, int variant, int split_k)
+{
+    if (!X || !hi_plane || !lo_plane || !scales || !Y) return FP6_ERR_NULL;
+    if (M <= 0 || M > (int64_t)1 << 24 || !shape_ok(N, K)) return FP6_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(scales) || !aligned16(Y) ||
+        !aligned16(workspace))
+        return FP6_ERR_ALIGN;
+    LinearPlan p;
+    if (!make_plan(M, N, K, variant, split_k, &p)) return FP6_ERR_VARIANT;
+    const size_t need = plan_workspace(p);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return FP6_ERR_WORKSPACE;
+    hipError_t e = (p.variant == FP6_VARIANT_DECODE)
+                       ? launch_decode(p, X, M, hi_plane, lo_plane, scales, N, K, Y, workspace, (hipStream_t)stream)
+                       : launch_gemm(p, X, M, hi_plane, lo_plane, scales, N, K, Y, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? FP6_OK : FP6_ERR_HIP;
+}
+
+int fp6_linear(const uint16_t* X, int64_t M, const void* hi_plane, const void* lo_plane, const uint16_t* scales,
+               int64_t N, int64_t K, uint16_t* Y, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return fp6_linear_variant(X, M, hi_plane, lo_plane, scales, N, K, Y, workspace, workspace_bytes, stream,
+                              FP6_VARIANT_AUTO, 0);
+}
+
+}  // extern "C"

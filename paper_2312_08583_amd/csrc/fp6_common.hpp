@@ -1,0 +1,90 @@
+// Device-side building blocks shared by the gfx950 kernels: vector types, the
+// 4+2 -> fp16 unpack (ZeroQuant(4+2) Sections 5.1-5.2) and the tile addressing of the
+// packed planes (layout version 1, described in include/fp6_linear.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fp6 {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kTile = 64;             // tile edge in n and in k
+constexpr int kHiTileBytes = 2048;    // 4-bit plane bytes per tile
+constexpr int kLoTileBytes = 1024;    // 2-bit plane bytes per tile
+constexpr int kHiTileVec = kHiTileBytes / 16;   // uint4 per tile
+constexpr int kLoTileVec = kLoTileBytes / 16;
+
+// bitwise select: mask bit 1 -> a, mask bit 0 -> b   (one v_bitop3_b32)
+__device__ __forceinline__ uint32_t bit_select(uint32_t a, uint32_t b, uint32_t mask)
+{
+    return __builtin_amdgcn_bitop3_b32(a, b, mask, 0xE4);
+}
+
+// Raw packed data of one 64x64 tile as held by one lane: 64 weights.
+struct TileRaw {
+    u32x4 hi0;   // fragments 0..3: one dword per fragment (8 sign+exponent sub-numbers)
+    u32x4 hi1;   // fragments 4..7
+    u32x4 lo;    // dword d: the mantissa sub-numbers of fragments 2d and 2d+1
+};
+
+// Three coalesced 128-bit loads per lane.  The weight stream is read exactly once, so
+// it is marked non-temporal to keep it from evicting X and the partial sums.
+__device__ __forceinline__ TileRaw load_tile(const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
+                                             size_t tile_index, int lane)
+{
+    TileRaw r;
+    const u32x4* h = hi + tile_index * kHiTileVec + lane;
+    r.hi0 = __builtin_nontemporal_load(h);
+    r.hi1 = __builtin_nontemporal_load(h + 64);
+    r.lo = __builtin_nontemporal_load(lo + tile_index * kLoTileVec + lane);
+    return r;
+}
+
+// f must be a compile-time constant after unrolling
+__device__ __forceinline__ uint32_t tile_hi_dword(const TileRaw& r, int f)
+{
+    return (f < 4) ? r.hi0[f & 3] : r.hi1[f & 3];
+}
+
+__device__ __forceinline__ uint32_t tile_lo_dword(const TileRaw& r, int f) { return r.lo[f >> 1]; }
+
+// Bias-shift unpack of one fragment (8 weights of one lane) into the four packed-fp16
+// registers of an MFMA 16x16x32 operand.  Pure bit padding (Section 5.2, Eq. 5): the
+// byte  s00eeemm  is the top byte of the fp16 pattern  s 00eee mm00000000, whose value is
+// the FP6 value times 2^-12.  H = the fragment's dword of the 4-bit plane, L = its dword
+// of the 2-bit plane already shifted right by 4*(f&1).
+//   byte b of H: bit0 sign(grp0) bit1 sign(grp1) bits4..2 exp(grp0) bits7..5 exp(grp1)
+//   byte b of L: bits1..0 mant(grp0) bits3..2 mant(grp1)
+// Byte b carries element j = 2*(b&1) + (b>>1) of its group: bytes 0 and 2 become the low
+// and high half of one operand register (elements 0,1), bytes 1 and 3 those of the next.
+__device__ __forceinline__ half8 unpack_fragment(uint32_t H, uint32_t L)
+{
+    // s g g e e e m m per byte (g = don't-care bits removed by the final masks)
+    uint32_t u0 = bit_select(H << 7, bit_select(H, L, 0x1C1C1C1Cu), 0x80808080u);
+    uint32_t u1 = bit_select(H << 6, bit_select(H >> 3, L >> 2, 0x1C1C1C1Cu), 0x80808080u);
+    u32x4 w;
+    w.x = (u0 << 8) & 0x9F009F00u;   // bytes 0,2 -> elements 0,1
+    w.y = u0 & 0x9F009F00u;          // bytes 1,3 -> elements 2,3
+    w.z = (u1 << 8) & 0x9F009F00u;   // elements 4,5
+    w.w = u1 & 0x9F009F00u;          // elements 6,7
+    return __builtin_bit_cast(half8, w);
+}
+
+__device__ __forceinline__ half8 unpack_tile_fragment(const TileRaw& r, int f)
+{
+    return unpack_fragment(tile_hi_dword(r, f), tile_lo_dword(r, f) >> (4 * (f & 1)));
+}
+
+// D(16x16, fp32) += A(16x32 fp16) * B(32x16 fp16).  Lane l supplies row l%16 of A and
+// column l%16 of B for the eight k values of group l/16, and holds D[4*(l/16)+r][l%16].
+__device__ __forceinline__ float4v mfma16x16x32(half8 a, half8 b, float4v c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+}  // namespace fp6

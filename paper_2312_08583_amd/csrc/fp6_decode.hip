@@ -1,0 +1,160 @@
+// Decode-shape kernel (M <= 16) of the W6A16 linear layer for gfx950.
+//
+// The work is a stream over the packed weight (0.75 byte per weight, Section 5.1):
+// a workgroup owns 64 output channels and one K-slice; its wavefronts take the slice's
+// 64x64 tiles round-robin, so the workgroup walks one contiguous region of each plane.
+// Per tile a lane issues three 128-bit loads (two of the 4-bit plane, one of the 2-bit
+// plane), pads the sub-numbers into fp16 operands in registers (bias shift, Section 5.2)
+// and feeds eight v_mfma_f32_16x16x32_f16 (weights = A, the <=16 rows of X = B, padded
+// with zero columns).  X is tiny and L2-resident, so each wavefront reads its 16-byte
+// operand slices of X directly.  Partial sums of the wavefronts are added in LDS; if K
+// is also split over workgroups the slices meet in an fp32 workspace and the workgroup
+// that arrives last adds them in slice order (deterministic) and applies the epilogue
+// Y = fp16(acc * S_n * 2^12) - the row scale after the accumulation (Section 5.2).
+#include "fp6_common.hpp"
+#include "fp6_internal.hpp"
+#include "fp6_reduce.hpp"
+
+namespace fp6 {
+
+struct XFrag {
+    half8 q0, q1;   // operand slices for the two 32-wide k blocks of a tile
+};
+
+__device__ __forceinline__ XFrag load_x(const uint16_t* __restrict__ xrow, int kt, bool valid)
+{
+    XFrag x;
+    if (valid) {
+        const half8* p = reinterpret_cast<const half8*>(xrow + (size_t)kt * kTile);
+        x.q0 = p[0];
+        x.q1 = p[4];   // +32 halfs
+    } else {
+        x.q0 = half8{0, 0, 0, 0, 0, 0, 0, 0};
+        x.q1 = x.q0;
+    }
+    return x;
+}
+
+__device__ __forceinline__ void tile_mac(const TileRaw& r, const XFrag& x, float4v acc[4])
+{
+#pragma unroll
+    for (int f = 0; f < 8; f++) {
+        half8 w = unpack_tile_fragment(r, f);
+        acc[f >> 1] = mfma16x16x32(w, (f & 1) ? x.q1 : x.q0, acc[f >> 1]);
+    }
+}
+
+template <int WAVES, int TS>
+__global__ __launch_bounds__(WAVES * 64) void decode_kernel(
+    const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
+    const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
+    float4v* __restrict__ partials, uint32_t* __restrict__ counters, int split_k)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int ktiles = K / kTile;
+    const int nblocks = N / kTile;
+    const int nb = blockIdx.x / split_k, s = blockIdx.x % split_k;
+    const int kt_per = ktiles / split_k;
+    const int kt_end = (s + 1) * kt_per;
+    const int m = lane & 15, g = lane >> 4;
+    const bool mvalid = m < M;
+    const uint16_t* xrow = X + (size_t)(mvalid ? m : 0) * K + g * 8;
+    const size_t tile0 = (size_t)nb * ktiles;
+
+    float4v acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; t++) acc[t] = float4v{0.f, 0.f, 0.f, 0.f};
+
+    // software pipeline: TS tiles in registers being consumed, the next TS in flight
+    TileRaw cur[TS], nxt[TS];
+    XFrag xc[TS], xn[TS];
+    int kt = s * kt_per + wave;
+#pragma unroll
+    for (int u = 0; u < TS; u++) {
+        const int k = kt + u * WAVES;
+        if (k < kt_end) {
+            cur[u] = load_tile(hi, lo, tile0 + k, lane);
+            xc[u] = load_x(xrow, k, mvalid);
+        }
+    }
+    while (kt < kt_end) {
+        const int ktn = kt + TS * WAVES;
+#pragma unroll
+        for (int u = 0; u < TS; u++) {
+            const int k = ktn + u * WAVES;
+            if (k < kt_end) {
+                nxt[u] = load_tile(hi, lo, tile0 + k, lane);
+                xn[u] = load_x(xrow, k, mvalid);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < TS; u++) {
+            if (kt + u * WAVES < kt_end) tile_mac(cur[u], xc[u], acc);
+        }
+#pragma unroll
+        for (int u = 0; u < TS; u++) {
+            cur[u] = nxt[u];
+            xc[u] = xn[u];
+        }
+        kt = ktn;
+    }
+
+    // ---- add the wavefronts' partial sums in LDS
+    __shared__ float4v red[WAVES][256];
+#pragma unroll
+    for (int t = 0; t < 4; t++) red[wave][t * 64 + lane] = acc[t];
+    __syncthreads();
+    const int tid = threadIdx.x;
+    float4v sum = float4v{0.f, 0.f, 0.f, 0.f};
+    if (tid < 256) {
+#pragma unroll
+        for (int w = 0; w < WAVES; w++) sum += red[w][tid];
+    }
+
+    // ---- add the K-slices of other workgroups (last arrival does it, in slice order)
+    if (split_k > 1) {
+        if (tid < 256) partials[((size_t)s * nblocks + nb) * 256 + tid] = sum;
+        if (!arrive_last(&counters[nb], (uint32_t)split_k)) return;
+        if (tid < 256) {
+            sum = float4v{0.f, 0.f, 0.f, 0.f};
+            for (int ss = 0; ss < split_k; ss++) sum += load_partial(&partials[((size_t)ss * nblocks + nb) * 256 + tid]);
+        }
+    }
+
+    // ---- epilogue: thread (t, l) holds rows n = 16t + 4(l/16) + r of column m = l%16
+    if (tid < 256) {
+        const int t = tid >> 6, l = tid & 63;
+        const int mm = l & 15;
+        if (mm < M) {
+            const int n = nb * kTile + t * 16 + (l >> 4) * 4;
+            const half4 sc = *reinterpret_cast<const half4*>(scales + n);
+            half4 y;
+#pragma unroll
+            for (int r = 0; r < 4; r++) y[r] = (_Float16)(sum[r] * ((float)sc[r] * 4096.0f));
+            *reinterpret_cast<half4*>(Y + (size_t)mm * N + n) = y;
+        }
+    }
+}
+
+template <int WAVES, int TS>
+static hipError_t launch_decode_t(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
+                                  const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
+                                  hipStream_t stream)
+{
+    uint32_t* counters = reinterpret_cast<uint32_t*>(workspace);
+    float4v* partials = reinterpret_cast<float4v*>(reinterpret_cast<char*>(workspace) + kCounterBytes);
+    const unsigned grid = (unsigned)((N / kTile) * p.split_k);
+    hipLaunchKernelGGL((decode_kernel<WAVES, TS>), dim3(grid), dim3(WAVES * 64), 0, stream, X, (int)M,
+                       (const u32x4*)hi, (const u32x4*)lo, scales, (int)N, (int)K, Y, partials, counters, p.split_k);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
+                         const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
+                         hipStream_t stream)
+{
+    if (p.waves == 8) return launch_decode_t<8, 1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+    return launch_decode_t<4, 2>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+}
+
+}  // namespace fp6

@@ -1,0 +1,41 @@
+// Host-side declarations shared by the translation units of the library.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace fp6 {
+
+// Workspace layout: [counters: kCounterBytes][fp32 partial sums]
+constexpr size_t kCounterBytes = 16384;
+constexpr int kMaxCounters = (int)(kCounterBytes / sizeof(uint32_t));
+
+hipError_t launch_quantize_pack(const uint16_t* W, int64_t N, int64_t K, void* hi, void* lo, uint16_t* scales,
+                                hipStream_t stream);
+hipError_t launch_unpack_codes(const void* hi, const void* lo, int64_t N, int64_t K, uint8_t* codes,
+                               hipStream_t stream);
+hipError_t launch_dequantize(const void* hi, const void* lo, const uint16_t* scales, int64_t N, int64_t K,
+                             uint16_t* W_hat, hipStream_t stream);
+
+// A fully resolved launch plan for fp6_linear.
+struct LinearPlan {
+    int variant;        // FP6_VARIANT_DECODE or FP6_VARIANT_GEMM
+    int split_k;        // K-slices handled by separate workgroups (>= 1)
+    int block_m;        // GEMM: rows of X per workgroup (32, 64 or 128); DECODE: 16
+    int waves;          // wavefronts per workgroup
+    size_t partial_bytes;   // fp32 partial sums needed in the workspace (0 if split_k == 1)
+    int counters;       // arrival counters used (0 if split_k == 1)
+};
+
+// Heuristic (or caller-forced) plan; returns false if the request is invalid for the shape.
+bool make_plan(int64_t M, int64_t N, int64_t K, int variant, int split_k, LinearPlan* plan);
+
+hipError_t launch_decode(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
+                         const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
+                         hipStream_t stream);
+hipError_t launch_gemm(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
+                       const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
+                       hipStream_t stream);
+
+}  // namespace fp6

@@ -1,0 +1,211 @@
+// Offline quantizer / packer (ZeroQuant(4+2) Section 4 Eq. 3, Section 5.1) and the two
+// plane-reading test utilities, for gfx950.
+#include "fp6_common.hpp"
+#include "fp6_internal.hpp"
+
+namespace fp6 {
+
+// ------------------------------------------------------------------ row scales
+// S_n = RNE_fp16(max_k |W[n,k]| / 28).  |w| of finite fp16 orders like its 15 magnitude
+// bits, so the maximum is taken on integers.  The quotient is one IEEE fp32 division
+// followed by one fp32->fp16 rounding; a double rounding cannot occur because amax/28
+// is either exact in fp16 or at least 2^-14 (relative) away from every fp16 midpoint.
+__global__ __launch_bounds__(256) void row_scale_kernel(const uint16_t* __restrict__ W, int64_t K,
+                                                         uint16_t* __restrict__ scales)
+{
+    const int64_t n = blockIdx.x;
+    const uint4* row = reinterpret_cast<const uint4*>(W + n * K);
+    const int64_t nvec = K / 8;
+    uint32_t amax = 0;
+    for (int64_t v = threadIdx.x; v < nvec; v += 256) {
+        uint4 d = row[v];
+        uint32_t w[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            amax = max(amax, w[i] & 0x7FFFu);
+            amax = max(amax, (w[i] >> 16) & 0x7FFFu);
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) amax = max(amax, (uint32_t)__shfl_xor((int)amax, off, 64));
+    __shared__ uint32_t s_max[4];
+    if ((threadIdx.x & 63) == 0) s_max[threadIdx.x >> 6] = amax;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        amax = max(max(s_max[0], s_max[1]), max(s_max[2], s_max[3]));
+        float a = (float)__builtin_bit_cast(_Float16, (uint16_t)amax);
+        _Float16 S = (_Float16)(a / 28.0f);
+        scales[n] = __builtin_bit_cast(uint16_t, S);
+    }
+}
+
+// Round-to-nearest E3M2 code of w / S (ties to the even code, saturating at 28).
+// q = |w|/S is one correctly rounded fp32 division: a quotient that is not exactly a
+// grid midpoint is at least 2^-17 (relative) away from it, far more than the 2^-24 the
+// division can move it, and an exact midpoint divides exactly - so rounding q decides
+// exactly as rounding the real quotient would.  On the E3M2 grid the spacing inside
+// the binade of q is 2^(e-2) (1/16 below 0.25), so the rounding is one rint of q/spacing.
+__device__ __forceinline__ uint32_t e3m2_code(uint16_t wbits, float S)
+{
+    const uint32_t sign = (wbits >> 15) << 5;
+    if (S == 0.0f) return sign;
+    float a = (float)__builtin_bit_cast(_Float16, (uint16_t)(wbits & 0x7FFFu));
+    float q = fminf(a / S, 28.0f);
+    int e = (int)((__builtin_bit_cast(uint32_t, q) >> 23) & 0xFF) - 127;   // floor(log2 q), q normal
+    e = max(e, -2);
+    float inv_step = __builtin_bit_cast(float, (uint32_t)(127 - (e - 2)) << 23);   // 2^-(e-2)
+    float step = __builtin_bit_cast(float, (uint32_t)(127 + (e - 2)) << 23);
+    float v = rintf(q * inv_step) * step;          // exact products (powers of two)
+    uint32_t vb = __builtin_bit_cast(uint32_t, v);
+    uint32_t mag;
+    if (v < 0.25f) {
+        mag = (uint32_t)(v * 16.0f);               // subnormal codes 0..3
+    } else {
+        uint32_t E = ((vb >> 23) & 0xFF) - 124;    // exponent + bias 3
+        mag = (E << 2) | ((vb >> 21) & 3);
+    }
+    return sign | mag;
+}
+
+// One thread = one lane slot of one tile (64 weights): reads its eight 8-element runs of
+// W, quantizes them, and writes its 32 + 16 bytes of the two planes.
+__global__ __launch_bounds__(256) void quantize_pack_kernel(const uint16_t* __restrict__ W, int64_t N, int64_t K,
+                                                             const uint16_t* __restrict__ scales,
+                                                             uint4* __restrict__ hi, uint4* __restrict__ lo)
+{
+    const int64_t slot = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t tile = slot >> 6;
+    const int lane = (int)(slot & 63);
+    const int64_t ktiles = K / kTile;
+    if (tile >= (N / kTile) * ktiles) return;
+    const int64_t nb = tile / ktiles, kb = tile % ktiles;
+    const int i = lane & 15, g = lane >> 4;
+
+    uint32_t hiw[8], low[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int f = 0; f < 8; f++) {
+        const int64_t n = nb * kTile + (f >> 1) * 16 + i;
+        const int64_t k = kb * kTile + (f & 1) * 32 + g * 8;
+        const float S = (float)__builtin_bit_cast(_Float16, scales[n]);
+        uint4 d = *reinterpret_cast<const uint4*>(W + n * K + k);
+        uint32_t w2[4] = {d.x, d.y, d.z, d.w};
+        uint32_t h = 0, l = 0;
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            uint16_t wb = (uint16_t)((e & 1) ? (w2[e >> 1] >> 16) : (w2[e >> 1] & 0xFFFFu));
+            uint32_t c = e3m2_code(wb, S);
+            const int grp = e >> 2, j = e & 3;
+            const int b = 2 * (j & 1) + (j >> 1);
+            const uint32_t s = c >> 5, ex = (c >> 2) & 7, m = c & 3;
+            h |= (s << grp | ex << (2 + 3 * grp)) << (8 * b);
+            l |= (m << (2 * grp)) << (8 * b);
+        }
+        hiw[f] = h;
+        low[f >> 1] |= l << (4 * (f & 1));
+    }
+    uint4* hp = hi + tile * kHiTileVec + lane;
+    hp[0] = make_uint4(hiw[0], hiw[1], hiw[2], hiw[3]);
+    hp[64] = make_uint4(hiw[4], hiw[5], hiw[6], hiw[7]);
+    lo[tile * kLoTileVec + lane] = make_uint4(low[0], low[1], low[2], low[3]);
+}
+
+// ------------------------------------------------------------------ plane readers
+// code of element e (0..7) of a fragment, from its two dwords (L already shifted by 4*(f&1))
+__device__ __forceinline__ uint32_t fragment_code(uint32_t H, uint32_t L, int e)
+{
+    const int grp = e >> 2, j = e & 3;
+    const int b = 2 * (j & 1) + (j >> 1);
+    const uint32_t hb = (H >> (8 * b)) & 0xFF, lb = (L >> (8 * b)) & 0xFF;
+    const uint32_t s = (hb >> grp) & 1, ex = (hb >> (2 + 3 * grp)) & 7, m = (lb >> (2 * grp)) & 3;
+    return s << 5 | ex << 2 | m;
+}
+
+__global__ __launch_bounds__(256) void unpack_codes_kernel(const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
+                                                            int64_t N, int64_t K, uint8_t* __restrict__ codes)
+{
+    const int64_t slot = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t tile = slot >> 6;
+    const int lane = (int)(slot & 63);
+    const int64_t ktiles = K / kTile;
+    if (tile >= (N / kTile) * ktiles) return;
+    const int64_t nb = tile / ktiles, kb = tile % ktiles;
+    const int i = lane & 15, g = lane >> 4;
+    TileRaw r = load_tile(hi, lo, (size_t)tile, lane);
+#pragma unroll
+    for (int f = 0; f < 8; f++) {
+        const int64_t n = nb * kTile + (f >> 1) * 16 + i;
+        const int64_t k = kb * kTile + (f & 1) * 32 + g * 8;
+        const uint32_t H = tile_hi_dword(r, f), L = tile_lo_dword(r, f) >> (4 * (f & 1));
+        uint32_t c0 = 0, c1 = 0;
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            c0 |= fragment_code(H, L, e) << (8 * e);
+            c1 |= fragment_code(H, L, 4 + e) << (8 * e);
+        }
+        *reinterpret_cast<uint2*>(codes + n * K + k) = make_uint2(c0, c1);
+    }
+}
+
+// W_hat = RNE_fp16(S * value(code)): the fp32 product of an 11-bit and a 3-bit
+// significand is exact, so the only rounding is the conversion to fp16.
+__global__ __launch_bounds__(256) void dequantize_kernel(const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
+                                                          const uint16_t* __restrict__ scales, int64_t N, int64_t K,
+                                                          uint16_t* __restrict__ W_hat)
+{
+    const int64_t slot = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t tile = slot >> 6;
+    const int lane = (int)(slot & 63);
+    const int64_t ktiles = K / kTile;
+    if (tile >= (N / kTile) * ktiles) return;
+    const int64_t nb = tile / ktiles, kb = tile % ktiles;
+    const int i = lane & 15, g = lane >> 4;
+    TileRaw r = load_tile(hi, lo, (size_t)tile, lane);
+#pragma unroll
+    for (int f = 0; f < 8; f++) {
+        const int64_t n = nb * kTile + (f >> 1) * 16 + i;
+        const int64_t k = kb * kTile + (f & 1) * 32 + g * 8;
+        const float S = (float)__builtin_bit_cast(_Float16, scales[n]);
+        const uint32_t H = tile_hi_dword(r, f), L = tile_lo_dword(r, f) >> (4 * (f & 1));
+        uint32_t out[4];
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            const uint32_t c = fragment_code(H, L, e);
+            const uint32_t ex = (c >> 2) & 7, m = c & 3;
+            // value = m/16 (subnormal) or (4+m) * 2^(ex-5)
+            float mag = ex ? (float)((4 + m) << (ex - 1)) * 0.0625f : (float)m * 0.0625f;
+            _Float16 hval = (_Float16)(S * mag);
+            uint32_t hb = __builtin_bit_cast(uint16_t, hval) | ((c >> 5) << 15);
+            if (e & 1) out[e >> 1] |= hb << 16; else out[e >> 1] = hb;
+        }
+        *reinterpret_cast<uint4*>(W_hat + n * K + k) = make_uint4(out[0], out[1], out[2], out[3]);
+    }
+}
+
+// ------------------------------------------------------------------ launchers
+static inline unsigned slot_blocks(int64_t N, int64_t K) { return (unsigned)(((N / kTile) * (K / kTile) * 64 + 255) / 256); }
+
+hipError_t launch_quantize_pack(const uint16_t* W, int64_t N, int64_t K, void* hi, void* lo, uint16_t* scales,
+                                hipStream_t stream)
+{
+    hipLaunchKernelGGL(row_scale_kernel, dim3((unsigned)N), dim3(256), 0, stream, W, K, scales);
+    hipLaunchKernelGGL(quantize_pack_kernel, dim3(slot_blocks(N, K)), dim3(256), 0, stream, W, N, K,
+                       (const uint16_t*)scales, (uint4*)hi, (uint4*)lo);
+    return hipGetLastError();
+}
+
+hipError_t launch_unpack_codes(const void* hi, const void* lo, int64_t N, int64_t K, uint8_t* codes, hipStream_t stream)
+{
+    hipLaunchKernelGGL(unpack_codes_kernel, dim3(slot_blocks(N, K)), dim3(256), 0, stream, (const u32x4*)hi,
+                       (const u32x4*)lo, N, K, codes);
+    return hipGetLastError();
+}
+
+hipError_t launch_dequantize(const void* hi, const void* lo, const uint16_t* scales, int64_t N, int64_t K,
+                             uint16_t* W_hat, hipStream_t stream)
+{
+    hipLaunchKernelGGL(dequantize_kernel, dim3(slot_blocks(N, K)), dim3(256), 0, stream, (const u32x4*)hi,
+                       (const u32x4*)lo, scales, N, K, W_hat);
+    return hipGetLastError();
+}
+
+}  // namespace fp6

@@ -1,0 +1,243 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by
+element on the same seeded inputs.  Bit-exact for scales, codes, planes and dequantized
+weights; Y within 2e-3 (see gpu_util.assert_y_close)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2312_08583_amd as P
+from oracle import fp6_oracle as O
+from paper_2312_08583_amd import inputs
+
+from gpu_util import assert_y_close, from_np16, oracle_reference, to_np16
+from layout_ref import pack_planes
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _quant(W):
+    hi, lo, sc = P.fp6_quantize_pack(W)
+    torch.cuda.synchronize()
+    return hi, lo, sc
+
+
+def _check_quant_bit_exact(Wnp16: np.ndarray):
+    """quantize on the GPU and compare scales / codes / planes / W_hat with the oracle."""
+    N, K = Wnp16.shape
+    W = from_np16(Wnp16)
+    hi, lo, sc = _quant(W)
+    codes_o, scales_o = O.quantize(Wnp16)
+    assert np.array_equal(to_np16(sc), scales_o)
+    codes_g = P.fp6_unpack_codes(hi, lo, N, K).cpu().numpy()
+    assert np.array_equal(codes_g, codes_o)
+    hi_o, lo_o = pack_planes(codes_o)
+    assert np.array_equal(hi.cpu().numpy(), hi_o)
+    assert np.array_equal(lo.cpu().numpy(), lo_o)
+    what_g = to_np16(P.fp6_dequantize(hi, lo, sc, N, K))
+    assert np.array_equal(what_g, O.dequantize(codes_o, scales_o))
+    return hi, lo, sc, codes_o, scales_o
+
+
+# ------------------------------------------------------------------ offline step
+
+def test_quantize_pack_config1_bit_exact():
+    W = inputs.workload_weight("cfg1_single", 0, device=DEV)
+    _check_quant_bit_exact(to_np16(W))
+
+
+def test_quantize_pack_outlier_weights_bit_exact():
+    W = inputs.weight(320, 704, seed=11, sigma=0.02, outlier_frac=0.001, device=DEV)
+    _check_quant_bit_exact(to_np16(W))
+
+
+def test_quantize_special_rows_bit_exact():
+    rng = np.random.default_rng(4)
+    N, K = 64, 128
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+    W[0] = 0                                                   # all-zero row, +0
+    W[1] = np.float16(-0.0)                                    # all -0
+    W[2] = 0; W[2, 5] = np.float16(6e-8); W[2, 6] = -np.float16(6e-8)   # amax/28 rounds to zero
+    W[3] = (rng.standard_normal(K) * 1e-6).astype(np.float16)  # subnormal weights, subnormal scale
+    W[4] = (rng.standard_normal(K) * 2000).astype(np.float16)  # large weights, S > 1
+    mags = np.array([O.e3m2_value(c) for c in range(32)])
+    mids = (mags[:-1] + mags[1:]) / 2
+    for r, S0 in [(5, 2.0 ** -8), (6, 2.0 ** -2), (7, 2.0 ** -13)]:        # exact ties, both signs
+        row = np.zeros(K)
+        row[0] = 28 * S0
+        row[1:32] = mids * S0
+        row[33:64] = -mids * S0
+        row[64:96] = mags * S0
+        row[96:128] = -mags * S0
+        W[r] = row.astype(np.float16)
+        assert np.array_equal(W[r].astype(np.float64), row)
+    W[8] = 0; W[8, 0] = np.float16(65504); W[8, 1] = np.float16(-65504); W[8, 2] = np.float16(30000)  # overflow of S*28
+    W[9] = np.float16(0.3335); W[9, 3] = np.float16(0.01)     # |w|/S slightly above 28: saturation
+    _check_quant_bit_exact(W.view(np.uint16))
+
+
+def test_quantize_every_finite_fp16_value_at_many_scales():
+    allw = np.arange(0, 0x7C00, dtype=np.uint16)
+    rng = np.random.default_rng(6)
+    amax_bits = [0x3C00, 0x2E66, 0x2C00, 0x3555, 0x0155, 0x0400, 0x7BFF, 0x1234, 0x0003, 0x5640] + \
+        rng.integers(0x0400, 0x7BFF, 54).tolist()
+    K = 63488 + 64 - 63488 % 64          # both signs of every finite value fit in one row
+    rows = np.zeros((64, K), np.uint16)
+    for r, ab in enumerate(amax_bits):
+        w = allw[allw <= ab]
+        row = np.concatenate([w, w | 0x8000])
+        rows[r, :row.size] = row
+        rows[r, row.size:] = ab
+    _check_quant_bit_exact(rows)
+
+
+# ------------------------------------------------------------------ planes
+
+def test_unpack_is_inverse_of_documented_layout():
+    rng = np.random.default_rng(8)
+    N, K = 192, 320
+    codes = rng.integers(0, 64, (N, K), dtype=np.uint8)
+    hi, lo = pack_planes(codes)
+    got = P.fp6_unpack_codes(torch.from_numpy(hi).to(DEV), torch.from_numpy(lo).to(DEV), N, K)
+    assert np.array_equal(got.cpu().numpy(), codes)
+    for c in range(64):
+        same = np.full((64, 64), c, np.uint8)
+        hi, lo = pack_planes(same)
+        got = P.fp6_unpack_codes(torch.from_numpy(hi).to(DEV), torch.from_numpy(lo).to(DEV), 64, 64)
+        assert np.array_equal(got.cpu().numpy(), same), c
+
+
+def test_quantize_of_dequantized_is_identity_on_gpu():
+    # rows hold S0 * value(c) for all 64 codes (incl. -0): quantize must return the codes,
+    # and dequantize must return the same fp16 bits
+    S0 = 2.0 ** -7
+    vals = np.array([abs(O.e3m2_value(c)) for c in range(64)]) * S0
+    bits = vals.astype(np.float16).view(np.uint16) | np.array([(c >> 5) << 15 for c in range(64)], np.uint16)
+    W = np.tile(bits, (64, 1))
+    hi, lo, sc = _quant(from_np16(W))
+    assert np.array_equal(P.fp6_unpack_codes(hi, lo, 64, 64).cpu().numpy(), np.tile(np.arange(64, dtype=np.uint8), (64, 1)))
+    assert np.array_equal(to_np16(P.fp6_dequantize(hi, lo, sc, 64, 64)), W)
+
+
+# ------------------------------------------------------------------ hot path
+
+VARIANTS = [(P.FP6_VARIANT_DECODE, 1), (P.FP6_VARIANT_DECODE, 2), (P.FP6_VARIANT_GEMM, 1), (P.FP6_VARIANT_GEMM, 2)]
+
+
+@pytest.mark.parametrize("variant,split", VARIANTS)
+def test_one_hot_rows_read_back_dequantized_weights_bit_exact(variant, split):
+    # X = one-hot rows: Y[m, n] must be RNE_fp16(S_n * value(code[n, k_m])) exactly - through
+    # the MFMA path, FP6 subnormals (fp16 subnormal operands after the bias shift) included
+    N, K = 128, 256
+    rng = np.random.default_rng(12)
+    codes = rng.integers(0, 64, (N, K), dtype=np.uint8)
+    codes[:, :64] = np.arange(64, dtype=np.uint8)[None, :]          # every code, every row
+    hi, lo = pack_planes(codes)
+    scales = np.linspace(0.004, 0.05, N).astype(np.float16).view(np.uint16)
+    what = O.dequantize(codes, scales)
+    hi_d, lo_d, sc_d = torch.from_numpy(hi).to(DEV), torch.from_numpy(lo).to(DEV), from_np16(scales)
+    ks = list(range(0, 64)) + [100, 255, 128, 191] + list(range(64, 76))
+    # a sum that starts at +0 cannot return -0: zero weights compare without their sign
+    what_cmp = np.where((what & 0x7FFF) == 0, 0, what).astype(np.uint16)
+    for k0 in range(0, len(ks), 16):
+        cols = ks[k0:k0 + 16]
+        X = torch.zeros((len(cols), K), dtype=torch.float16, device=DEV)
+        for m, k in enumerate(cols):
+            X[m, k] = 1.0
+        if variant == P.FP6_VARIANT_GEMM:
+            X = torch.cat([X, X, X[:1]])                           # M = 33: ragged
+        Y = P.fp6_linear_variant(X, hi_d, lo_d, sc_d, N, K, variant, split)
+        torch.cuda.synchronize()
+        Yb = to_np16(Y)
+        for m, k in enumerate(cols):
+            assert np.array_equal(Yb[m], what[:, k]), (m, k)
+
+
+@pytest.mark.parametrize("M", [1, 3, 16])
+@pytest.mark.parametrize("split", [1, 2, 4])
+def test_decode_tiny_shapes_vs_bruteforce_oracle(M, split):
+    N, K = 256, 256
+    W = inputs.weight(N, K, seed=100 + M, sigma=0.02, outlier_frac=0.001, device=DEV)
+    X = inputs.activation(M, K, seed=200 + M, device=DEV)
+    hi, lo, sc = _quant(W)
+    _, _, Yref = oracle_reference(W, X)
+    Y = P.fp6_linear_variant(X, hi, lo, sc, N, K, P.FP6_VARIANT_DECODE, split)
+    assert_y_close(Y, Yref, (M, split))
+
+
+@pytest.mark.parametrize("M", [1, 17, 33, 64, 100, 129, 300])
+@pytest.mark.parametrize("split", [1, 2])
+def test_gemm_shapes_vs_oracle(M, split):
+    N, K = 320, 512           # N not a multiple of 256: the last workgroup has idle wavefronts
+    W = inputs.weight(N, K, seed=300 + M, sigma=0.02, outlier_frac=0.001, device=DEV)
+    X = inputs.activation(M, K, seed=400 + M, device=DEV)
+    hi, lo, sc = _quant(W)
+    _, _, Yref = oracle_reference(W, X)
+    Y = P.fp6_linear_variant(X, hi, lo, sc, N, K, P.FP6_VARIANT_GEMM, split)
+    assert_y_close(Y, Yref, (M, split))
+
+
+def test_config1_full_matrix():
+    W = inputs.workload_weight("cfg1_single", 0, device=DEV)
+    X = inputs.activation(1, 1024, seed=inputs.workload_seed("cfg1_single", 900), device=DEV)
+    hi, lo, sc, codes_o, scales_o = _check_quant_bit_exact(to_np16(W))
+    Yref = O.linear(to_np16(X), codes_o, scales_o)
+    Y = P.fp6_linear(X, hi, lo, sc, 1024, 1024)
+    assert_y_close(Y, Yref, "cfg1")
+
+
+def test_constant_code_closed_form():
+    # all codes = c, X = ones: Y = S * value(c) * K exactly representable
+    N, K = 64, 256
+    for c in [1, 12, 31, 45, 63]:
+        hi, lo = pack_planes(np.full((N, K), c, np.uint8))
+        sc = torch.full((N,), 2.0 ** -6, dtype=torch.float16, device=DEV)
+        X = torch.ones((2, K), dtype=torch.float16, device=DEV)
+        for variant in (P.FP6_VARIANT_DECODE, P.FP6_VARIANT_GEMM):
+            Y = P.fp6_linear_variant(X, torch.from_numpy(hi).to(DEV), torch.from_numpy(lo).to(DEV), sc, N, K, variant, 1)
+            assert torch.all(Y.double() == 2.0 ** -6 * O.e3m2_value(c) * K), (c, variant)
+
+
+def test_split_and_unsplit_agree_and_workspace_is_reusable():
+    N, K, M = 512, 2048, 8
+    W = inputs.weight(N, K, seed=31, sigma=0.02, outlier_frac=0.001, device=DEV)
+    hi, lo, sc = _quant(W)
+    ws = P.new_workspace(P.fp6_linear_variant_workspace_bytes(M, N, K, P.FP6_VARIANT_DECODE, 8), DEV)
+    ys = []
+    for it in range(6):
+        X = inputs.activation(M, K, seed=500 + it, device=DEV)
+        Y1 = P.fp6_linear_variant(X, hi, lo, sc, N, K, P.FP6_VARIANT_DECODE, 1)
+        Y8 = P.fp6_linear_variant(X, hi, lo, sc, N, K, P.FP6_VARIANT_DECODE, 8, workspace=ws)
+        Y8b = P.fp6_linear_variant(X, hi, lo, sc, N, K, P.FP6_VARIANT_DECODE, 8, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(Y8, Y8b)                       # deterministic, counters were reset
+        # split and unsplit differ only by fp32 summation order: within one fp16 ulp-ish
+        d = (Y1.float() - Y8.float()).abs().max().item()
+        assert d <= 2e-3 * Y1.float().abs().max().item()
+        ys.append(Y8)
+    assert torch.count_nonzero(ws[:P.binding.FP6_WORKSPACE_COUNTER_BYTES]).item() == 0
+    assert not torch.equal(ys[0], ys[1])
+
+
+def test_linearity():
+    N, K, M = 256, 1024, 16
+    W = inputs.weight(N, K, seed=41, device=DEV)
+    hi, lo, sc = _quant(W)
+    X1 = inputs.activation(M, K, seed=42, device=DEV)
+    X2 = inputs.activation(M, K, seed=43, device=DEV)
+    Ya = P.fp6_linear(X1, hi, lo, sc, N, K).float() + P.fp6_linear(X2, hi, lo, sc, N, K).float()
+    Yb = P.fp6_linear((X1.float() + X2.float()).half(), hi, lo, sc, N, K).float()
+    assert (Ya - Yb).abs().max().item() <= 4e-3 * Yb.abs().max().item()
+
+
+@pytest.mark.parametrize("M", [1, 4, 16, 32, 128])
+def test_llama7b_qkvo_full_matrix(M):
+    N = K = 4096
+    W = inputs.workload_weight("cfg2_llama7b", 0, device=DEV)
+    X = inputs.activation(M, K, seed=inputs.workload_seed("cfg2_llama7b", 900 + M), device=DEV)
+    hi, lo, sc = _quant(W)
+    codes_o, scales_o, Yref = oracle_reference(W, X)
+    assert np.array_equal(to_np16(sc), scales_o)
+    assert np.array_equal(P.fp6_unpack_codes(hi, lo, N, K).cpu().numpy(), codes_o)
+    Y = P.fp6_linear(X, hi, lo, sc, N, K)
+    assert_y_close(Y, Yref, M)
