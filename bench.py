@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the W6A16 fp6_linear hot path on one MI355X.
+
+Workload (BASELINE config 5): a 34B-class decoder stack - 48 layers, hidden 8192, MLP
+22016, grouped-query attention (k/v projections 1024 x 8192) - with every linear layer
+(q, k, v, o, gate, up, down) run as fp6_linear on its own packed FP6 weight.  One "step"
+is one pass over all 336 linears (24.9 GB of packed weight, so the pass is cold in HBM
+by construction).  Two legs are timed: M=1 (decode, HBM-bound: GB/s counting 0.75 byte
+per weight) and M=512 (prefill, MFMA-bound: TFLOP/s counting 2*M*N*K).  `value` is the
+M=1 leg; the M=512 leg is reported in the same JSON line under "m512".
+
+Inputs are seeded synthetic tensors (paper_2312_08583_amd/inputs.py), resident in HBM
+before the timed region.  A pass is captured once into a HIP graph and replayed, so the
+timed region holds the kernels and nothing else.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_FP16_PEAK_TFLOPS = 2500.0
+WORKLOAD = "cfg5_34b_stack"
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=0, help="layers of the stack (0 = all 48)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-fp16-baseline", action="store_true")
+    ap.add_argument("--legs", default="1,512", help="comma-separated M values to time")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2312_08583_amd as P
+    from paper_2312_08583_amd import inputs
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = inputs.WORKLOADS[WORKLOAD]
+    shapes = cfg["shapes"]
+    layers = args.layers or cfg["layers"]
+
+    # ---- build the stack: seeded weights -> packed planes (offline step, untimed)
+    t0 = time.time()
+    stack = []            # per layer: list of (N, K, hi, lo, scales)
+    for layer in range(layers):
+        mats = []
+        for si, (_, N, K) in enumerate(shapes):
+            W = inputs.workload_weight(WORKLOAD, si, layer=layer, device=dev)
+            hi, lo, sc = P.fp6_quantize_pack(W)
+            mats.append((N, K, hi, lo, sc))
+            del W
+        stack.append(mats)
+    torch.cuda.synchronize()
+    build_s = time.time() - t0
+    weights_per_pass = sum(N * K for mats in stack for (N, K, *_) in mats)
+    launches = sum(len(m) for m in stack)
+
+    def make_leg(M):
+        xs = {K: inputs.activation(M, K, seed=inputs.workload_seed(WORKLOAD, 9000 + M + K), device=dev)
+              for K in sorted({K for (_, _, K) in shapes})}
+        ys = {N: torch.empty((M, N), dtype=torch.float16, device=dev) for N in sorted({N for (_, N, _) in shapes})}
+        need = max(P.fp6_linear_workspace_bytes(M, N, K) for (_, N, K) in shapes)
+        ws = P.new_workspace(max(need, 16), dev)
+
+        def one_pass():
+            for mats in stack:
+                for (N, K, hi, lo, sc) in mats:
+                    P.fp6_linear(xs[K], hi, lo, sc, N, K, out=ys[N], workspace=ws)
+        return one_pass, ys
+
+    def time_passes(one_pass, steps, warmup):
+        # capture one pass in a graph (eager pass first: module load, workspace touch)
+        one_pass()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            one_pass()
+        for _ in range(warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps      # ms per pass
+
+    legs = [int(m) for m in args.legs.split(",")]
+    res = {}
+    for M in legs:
+        one_pass, _ = make_leg(M)
+        ms = time_passes(one_pass, args.steps, args.warmup)
+        res[M] = dict(ms_per_step=ms,
+                      gbs=0.75 * weights_per_pass / (ms * 1e-3) / 1e9,
+                      tflops=2.0 * M * weights_per_pass / (ms * 1e-3) / 1e12)
+
+    # ---- fp16 dense GEMM on the same GPU, same stack (context, not the target)
+    fp16 = None
+    if not args.no_fp16_baseline:
+        dense = [[P.fp6_dequantize(hi, lo, sc, N, K) for (N, K, hi, lo, sc) in mats] for mats in stack]
+        fp16 = {}
+        for M in legs:
+            xs = {K: inputs.activation(M, K, seed=inputs.workload_seed(WORKLOAD, 9000 + M + K), device=dev)
+                  for K in sorted({K for (_, _, K) in shapes})}
+
+            def dense_pass():
+                for mats, ws_ in zip(stack, dense):
+                    for (N, K, *_), Wd in zip(mats, ws_):
+                        torch.matmul(xs[K], Wd.t())
+            for _ in range(2):
+                dense_pass()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            n = max(3, args.steps // 4)
+            e0.record()
+            for _ in range(n):
+                dense_pass()
+            e1.record()
+            torch.cuda.synchronize()
+            fp16[str(M)] = dict(ms_per_step=e0.elapsed_time(e1) / n)
+        del dense
+
+    # ---- CPU oracle on a bounded sample of the same workload (reported baseline)
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import fp6_oracle as O
+        sample = []
+        for si, (_, N, K) in enumerate(shapes):
+            W = inputs.workload_weight(WORKLOAD, si, layer=0, device=dev).cpu()
+            codes, scales = O.quantize(W.view(torch.int16).numpy().view(np.uint16))     # untimed set-up
+            sample.append((N, K, codes, scales))
+        xs = {K: inputs.activation(1, K, seed=inputs.workload_seed(WORKLOAD, 9001 + K), device="cpu")
+              .view(torch.int16).numpy().view(np.uint16) for K in sorted({K for (_, _, K) in shapes})}
+        best = None
+        for _ in range(3):
+            t0 = time.time()
+            for (N, K, codes, scales) in sample:
+                O.linear(xs[K], codes, scales)
+            dt = time.time() - t0
+            best = dt if best is None else min(best, dt)
+        wsample = sum(N * K for (N, K, *_) in sample)
+        cpu = dict(value=0.75 * wsample / best / 1e9, unit="GB/s", cores=O.threads(), kind="oracle",
+                   sample="layer 0 of the stack (7 linears, %.0f M weights) at M=1, oracle fp6o_linear, best of 3; "
+                          "oracle quantization of the sample not timed" % (wsample / 1e6))
+
+    lead = res[legs[0]]
+    out = {
+        "metric": "fp6_linear achieved HBM GB/s (M=1) and TFLOP/s (M=512) vs roofline, 1 MI355X",
+        "value": lead["gbs"] if legs[0] <= 118 else lead["tflops"],
+        "unit": "GB/s" if legs[0] <= 118 else "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": lead["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "%s: %d layers x 7 fp6_linear (q,k,v,o,gate,up,down; hidden 8192, MLP 22016, GQA kv 1024), "
+                               "M=%d, %.2f G weights per step" % (WORKLOAD, layers, legs[0], weights_per_pass / 1e9),
+                   "launches_per_step": launches, "build_seconds": round(build_s, 1)},
+        "roofline": ({"bound": "hbm", "achieved": lead["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                      "frac": lead["gbs"] / HBM_PEAK_GBS, "traffic": None,
+                      "kernel": "decode_kernel (M<=16), all %d launches of a step" % launches}
+                     if legs[0] <= 118 else
+                     {"bound": "mfma", "achieved": lead["tflops"], "peak": MFMA_FP16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                      "frac": lead["tflops"] / MFMA_FP16_PEAK_TFLOPS, "traffic": None,
+                      "kernel": "gemm_kernel, all %d launches of a step" % launches}),
+        "cpu_baseline": cpu,
+    }
+    if 512 in res and legs[0] != 512:
+        r = res[512]
+        out["m512"] = {"value": r["tflops"], "unit": "TFLOP/s", "ms_per_step": r["ms_per_step"],
+                       "roofline": {"bound": "mfma", "achieved": r["tflops"], "peak": MFMA_FP16_PEAK_TFLOPS,
+                                    "unit": "TFLOP/s", "frac": r["tflops"] / MFMA_FP16_PEAK_TFLOPS, "traffic": None,
+                                    "kernel": "gemm_kernel (block_m 128), all %d launches of a step" % launches}}
+    if fp16 is not None:
+        out["fp16_dense_baseline"] = {"kind": "torch.matmul (hipBLASLt) on the dequantized fp16 weights, same stack",
+                                      "ms_per_step": {m: v["ms_per_step"] for m, v in fp16.items()}}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -33,7 +33,8 @@
  * at (nn, kk) = (n % 64, k % 64) belongs to
  *     lane      l = 16 * ((kk % 32) / 8) + (nn % 16)          (0..63, one wavefront)
  *     fragment  f = 2 * (nn / 16) + (kk / 32)                 (0..7)
- *     element   e = kk % 8  =  4 * grp + b   (grp = e / 4, b = e % 4)
+ *     element   e = kk % 8  =  4 * grp + j   (grp = e / 4, j = e % 4), kept in byte
+ *               b = 2 * (j % 2) + j / 2 of its dword
  *   so that one lane's eight elements of a fragment are the eight consecutive-k fp16
  *   operands that lane feeds to v_mfma_f32_16x16x32_f16 for a 16(n) x 32(k) block.
  *   4-bit plane: byte ti*2048 + (f/4)*1024 + l*16 + (f%4)*4 + b holds, for the two
@@ -149,7 +150,15 @@ int fp6_linear(const uint16_t *X, int64_t M, const void *hi_plane, const void *l
  * workgroups chosen by the caller (tuning sweeps; tests that compare split and unsplit
  * results).  variant = FP6_VARIANT_AUTO and split_k = 0 reproduce fp6_linear.
  * split_k must divide K/64.  The workspace needed is fp6_linear_variant_workspace_bytes.
+ * Bits 8 and up of `variant` carry optional tuning hints (0 = automatic):
+ *   FP6_HINT_WAVES(w)   wavefronts per workgroup, decode family: 4 or 8
+ *   FP6_HINT_DEPTH(d)   tiles in the per-wavefront prefetch ring: 2..4 (decode), 3..4 (gemm)
+ *   FP6_HINT_BLOCK_M(b) rows of X per workgroup, gemm family: 32, 64 or 128
+ * An unsupported combination returns FP6_ERR_VARIANT.
  */
+#define FP6_HINT_WAVES(w) ((int)(w) << 8)
+#define FP6_HINT_DEPTH(d) ((int)(d) << 12)
+#define FP6_HINT_BLOCK_M(b) (((int)(b) / 16) << 16)
 size_t fp6_linear_variant_workspace_bytes(int64_t M, int64_t N, int64_t K, int variant, int split_k);
 int fp6_linear_variant(const uint16_t *X, int64_t M, const void *hi_plane, const void *lo_plane,
                        const uint16_t *scales, int64_t N, int64_t K, uint16_t *Y,

@@ -14,16 +14,15 @@ static bool shape_ok(int64_t N, int64_t K)
            K <= (int64_t)1 << 30 && N * K <= (int64_t)1 << 40;
 }
 
-// smallest divisor d of `ktiles` with units*d >= target and ktiles/d >= min_tiles; if no
-// divisor reaches the target, the largest one that keeps min_tiles per slice.
-static int pick_split(int64_t units, int64_t ktiles, int64_t target, int64_t min_tiles)
+// largest divisor d of `ktiles` with units*d <= capacity (workgroups that can be resident
+// at once: a second round of workgroups costs more than it gains) and ktiles/d >= min_tiles
+static int pick_split(int64_t units, int64_t ktiles, int64_t capacity, int64_t min_tiles)
 {
     int best = 1;
     for (int64_t d = 1; d <= ktiles; d++) {
         if (ktiles % d) continue;
-        if (ktiles / d < min_tiles) break;
+        if (ktiles / d < min_tiles || units * d > capacity) break;
         best = (int)d;
-        if (units * d >= target) break;
     }
     return best;
 }
@@ -31,6 +30,9 @@ static int pick_split(int64_t units, int64_t ktiles, int64_t target, int64_t min
 bool make_plan(int64_t M, int64_t N, int64_t K, int variant, int split_k, LinearPlan* plan)
 {
     const int64_t ktiles = K / FP6_TILE, nblocks = N / FP6_TILE;
+    // tuning hints ride in the upper bits of `variant`; 0 = automatic
+    const int hint_waves = (variant >> 8) & 0xF, hint_depth = (variant >> 12) & 0xF, hint_bm = ((variant >> 16) & 0xFF) * 16;
+    variant &= 0xFF;
     if (variant == FP6_VARIANT_AUTO) variant = (M <= 16) ? FP6_VARIANT_DECODE : FP6_VARIANT_GEMM;
     if (variant != FP6_VARIANT_DECODE && variant != FP6_VARIANT_GEMM) return false;
     if (variant == FP6_VARIANT_DECODE && M > 16) return false;
@@ -40,19 +42,26 @@ bool make_plan(int64_t M, int64_t N, int64_t K, int variant, int split_k, Linear
     p.variant = variant;
     int64_t tiles, regs_per_tile;
     if (variant == FP6_VARIANT_DECODE) {
+        if ((hint_waves && hint_waves != 4 && hint_waves != 8) || (hint_depth && (hint_depth < 2 || hint_depth > 4)) || hint_bm)
+            return false;
         p.block_m = 16;
-        p.waves = 4;
+        p.waves = hint_waves ? hint_waves : 4;
+        p.depth = hint_depth ? hint_depth : 4;
         tiles = nblocks;
         regs_per_tile = 256;                       // float4 per output tile (64 x 16 fp32)
-        // ~4 workgroups per compute unit, at least two tiles per wavefront
-        p.split_k = split_k ? split_k : pick_split(nblocks, ktiles, 1024, 2 * p.waves);
+        // up to 3 workgroups per compute unit are resident; at least two tiles per wavefront
+        p.split_k = split_k ? split_k : pick_split(nblocks, ktiles, 768, 2 * p.waves);
     } else {
-        p.block_m = M <= 32 ? 32 : (M <= 64 ? 64 : 128);
+        if (hint_waves || (hint_depth && hint_depth != 3 && hint_depth != 4) ||
+            (hint_bm && hint_bm != 32 && hint_bm != 64 && hint_bm != 128))
+            return false;
+        p.block_m = hint_bm ? hint_bm : (M <= 32 ? 32 : (M <= 64 ? 64 : 128));
         p.waves = 4;
+        p.depth = hint_depth ? hint_depth : 4;
         const int64_t mblk = (M + p.block_m - 1) / p.block_m, nblk = (nblocks + 3) / 4;
         tiles = mblk * nblk;
         regs_per_tile = (int64_t)(p.block_m / 16) * 4 * 256;
-        p.split_k = split_k ? split_k : pick_split(tiles, ktiles, 256, 16);
+        p.split_k = split_k ? split_k : pick_split(tiles, ktiles, 512, 16);
     }
     if (p.split_k > 1) {
         if (tiles > kMaxCounters) {

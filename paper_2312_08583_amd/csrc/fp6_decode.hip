@@ -44,7 +44,9 @@ __device__ __forceinline__ void tile_mac(const TileRaw& r, const XFrag& x, float
     }
 }
 
-template <int WAVES, int TS>
+// D = depth of the per-wavefront ring of tiles in flight (D-1 tiles are being fetched
+// while one is consumed).  The ring is indexed with compile-time constants only.
+template <int WAVES, int D>
 __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
     const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
@@ -65,38 +67,34 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
 #pragma unroll
     for (int t = 0; t < 4; t++) acc[t] = float4v{0.f, 0.f, 0.f, 0.f};
 
-    // software pipeline: TS tiles in registers being consumed, the next TS in flight
-    TileRaw cur[TS], nxt[TS];
-    XFrag xc[TS], xn[TS];
-    int kt = s * kt_per + wave;
+    // this wavefront's tiles: kt0, kt0 + WAVES, ...  (cnt of them, possibly none)
+    const int kt0 = s * kt_per + wave;
+    const int cnt = (kt_end - kt0 + WAVES - 1) / WAVES;
+    if (cnt > 0) {
+        TileRaw raw[D];
+        XFrag xf[D];
 #pragma unroll
-    for (int u = 0; u < TS; u++) {
-        const int k = kt + u * WAVES;
-        if (k < kt_end) {
-            cur[u] = load_tile(hi, lo, tile0 + k, lane);
-            xc[u] = load_x(xrow, k, mvalid);
-        }
-    }
-    while (kt < kt_end) {
-        const int ktn = kt + TS * WAVES;
-#pragma unroll
-        for (int u = 0; u < TS; u++) {
-            const int k = ktn + u * WAVES;
-            if (k < kt_end) {
-                nxt[u] = load_tile(hi, lo, tile0 + k, lane);
-                xn[u] = load_x(xrow, k, mvalid);
+        for (int u = 0; u < D - 1; u++) {
+            if (u < cnt) {
+                const int k = kt0 + u * WAVES;
+                raw[u] = load_tile(hi, lo, tile0 + k, lane);
+                xf[u] = load_x(xrow, k, mvalid);
             }
         }
+        for (int j0 = 0; j0 < cnt; j0 += D) {
 #pragma unroll
-        for (int u = 0; u < TS; u++) {
-            if (kt + u * WAVES < kt_end) tile_mac(cur[u], xc[u], acc);
+            for (int u = 0; u < D; u++) {
+                const int j = j0 + u;
+                if (j < cnt) {
+                    if (j + D - 1 < cnt) {      // refill the slot consumed one step ago
+                        const int k = kt0 + (j + D - 1) * WAVES;
+                        raw[(u + D - 1) % D] = load_tile(hi, lo, tile0 + k, lane);
+                        xf[(u + D - 1) % D] = load_x(xrow, k, mvalid);
+                    }
+                    tile_mac(raw[u], xf[u], acc);
+                }
+            }
         }
-#pragma unroll
-        for (int u = 0; u < TS; u++) {
-            cur[u] = nxt[u];
-            xc[u] = xn[u];
-        }
-        kt = ktn;
     }
 
     // ---- add the wavefronts' partial sums in LDS
@@ -113,11 +111,12 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
 
     // ---- add the K-slices of other workgroups (last arrival does it, in slice order)
     if (split_k > 1) {
-        if (tid < 256) partials[((size_t)s * nblocks + nb) * 256 + tid] = sum;
+        if (tid < 256) store_partial(partial_window(partials + ((size_t)s * nblocks + nb) * 256, 4096), tid, sum);
         if (!arrive_last(&counters[nb], (uint32_t)split_k)) return;
         if (tid < 256) {
             sum = float4v{0.f, 0.f, 0.f, 0.f};
-            for (int ss = 0; ss < split_k; ss++) sum += load_partial(&partials[((size_t)ss * nblocks + nb) * 256 + tid]);
+            for (int ss = 0; ss < split_k; ss++)
+                sum += load_partial(partial_window(partials + ((size_t)ss * nblocks + nb) * 256, 4096), tid);
         }
     }
 
@@ -136,7 +135,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     }
 }
 
-template <int WAVES, int TS>
+template <int WAVES, int D>
 static hipError_t launch_decode_t(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
                                   const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                                   hipStream_t stream)
@@ -144,7 +143,7 @@ static hipError_t launch_decode_t(const LinearPlan& p, const uint16_t* X, int64_
     uint32_t* counters = reinterpret_cast<uint32_t*>(workspace);
     float4v* partials = reinterpret_cast<float4v*>(reinterpret_cast<char*>(workspace) + kCounterBytes);
     const unsigned grid = (unsigned)((N / kTile) * p.split_k);
-    hipLaunchKernelGGL((decode_kernel<WAVES, TS>), dim3(grid), dim3(WAVES * 64), 0, stream, X, (int)M,
+    hipLaunchKernelGGL((decode_kernel<WAVES, D>), dim3(grid), dim3(WAVES * 64), 0, stream, X, (int)M,
                        (const u32x4*)hi, (const u32x4*)lo, scales, (int)N, (int)K, Y, partials, counters, p.split_k);
     return hipGetLastError();
 }
@@ -153,8 +152,14 @@ hipError_t launch_decode(const LinearPlan& p, const uint16_t* X, int64_t M, cons
                          const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                          hipStream_t stream)
 {
-    if (p.waves == 8) return launch_decode_t<8, 1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-    return launch_decode_t<4, 2>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+    switch (p.waves * 10 + p.depth) {
+        case 42: return launch_decode_t<4, 2>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        case 43: return launch_decode_t<4, 3>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        case 82: return launch_decode_t<8, 2>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        case 83: return launch_decode_t<8, 3>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        case 84: return launch_decode_t<8, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        default: return launch_decode_t<4, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+    }
 }
 
 }  // namespace fp6

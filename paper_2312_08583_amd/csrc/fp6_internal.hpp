@@ -24,6 +24,7 @@ struct LinearPlan {
     int split_k;        // K-slices handled by separate workgroups (>= 1)
     int block_m;        // GEMM: rows of X per workgroup (32, 64 or 128); DECODE: 16
     int waves;          // wavefronts per workgroup
+    int depth;          // tiles in the per-wavefront prefetch ring
     size_t partial_bytes;   // fp32 partial sums needed in the workspace (0 if split_k == 1)
     int counters;       // arrival counters used (0 if split_k == 1)
 };
