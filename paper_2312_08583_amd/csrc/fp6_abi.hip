@@ -52,16 +52,16 @@ bool make_plan(int64_t M, int64_t N, int64_t K, int variant, int split_k, Linear
         // up to 3 workgroups per compute unit are resident; at least two tiles per wavefront
         p.split_k = split_k ? split_k : pick_split(nblocks, ktiles, 768, 2 * p.waves);
     } else {
-        if (hint_waves || (hint_depth && hint_depth != 3 && hint_depth != 4) ||
-            (hint_bm && hint_bm != 32 && hint_bm != 64 && hint_bm != 128))
-            return false;
+        if (hint_waves || hint_depth || (hint_bm && hint_bm != 32 && hint_bm != 64 && hint_bm != 128)) return false;
+        if (M * K * 2 >= ((int64_t)1 << 32)) return false;   // X is addressed with 32-bit lane offsets
         p.block_m = hint_bm ? hint_bm : (M <= 32 ? 32 : (M <= 64 ? 64 : 128));
-        p.waves = 4;
-        p.depth = hint_depth ? hint_depth : 4;
-        const int64_t mblk = (M + p.block_m - 1) / p.block_m, nblk = (nblocks + 3) / 4;
+        p.waves = 8;
+        p.depth = p.block_m == 128 ? 3 : 4;
+        const int64_t mblk = (M + p.block_m - 1) / p.block_m, nblk = (nblocks + 7) / 8;
         tiles = mblk * nblk;
-        regs_per_tile = (int64_t)(p.block_m / 16) * 4 * 256;
-        p.split_k = split_k ? split_k : pick_split(tiles, ktiles, 512, 16);
+        regs_per_tile = (int64_t)(p.block_m / 16) * 4 * 512;
+        // one workgroup (eight wavefronts) per compute unit is resident
+        p.split_k = split_k ? split_k : pick_split(tiles, ktiles, 256, 16);
     }
     if (p.split_k > 1) {
         if (tiles > kMaxCounters) {

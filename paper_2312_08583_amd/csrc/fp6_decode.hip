@@ -21,17 +21,14 @@ struct XFrag {
     half8 q0, q1;   // operand slices for the two 32-wide k blocks of a tile
 };
 
-__device__ __forceinline__ XFrag load_x(const uint16_t* __restrict__ xrow, int kt, bool valid)
+// Lanes whose column m is past M read row M-1 instead: the MFMA columns are independent,
+// so those columns only produce values that are never stored.
+__device__ __forceinline__ XFrag load_x(const uint16_t* __restrict__ xrow, int kt)
 {
     XFrag x;
-    if (valid) {
-        const half8* p = reinterpret_cast<const half8*>(xrow + (size_t)kt * kTile);
-        x.q0 = p[0];
-        x.q1 = p[4];   // +32 halfs
-    } else {
-        x.q0 = half8{0, 0, 0, 0, 0, 0, 0, 0};
-        x.q1 = x.q0;
-    }
+    const half8* p = reinterpret_cast<const half8*>(xrow + (size_t)kt * kTile);
+    x.q0 = p[0];
+    x.q1 = p[4];   // +32 halfs
     return x;
 }
 
@@ -59,8 +56,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     const int kt_per = ktiles / split_k;
     const int kt_end = (s + 1) * kt_per;
     const int m = lane & 15, g = lane >> 4;
-    const bool mvalid = m < M;
-    const uint16_t* xrow = X + (size_t)(mvalid ? m : 0) * K + g * 8;
+    const uint16_t* xrow = X + (size_t)min(m, M - 1) * K + g * 8;
     const size_t tile0 = (size_t)nb * ktiles;
 
     float4v acc[4];
@@ -73,26 +69,35 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     if (cnt > 0) {
         TileRaw raw[D];
         XFrag xf[D];
+        // prologue: tiles 0 .. D-2 (clamped: a short wavefront re-reads its last tile)
 #pragma unroll
         for (int u = 0; u < D - 1; u++) {
-            if (u < cnt) {
-                const int k = kt0 + u * WAVES;
-                raw[u] = load_tile(hi, lo, tile0 + k, lane);
-                xf[u] = load_x(xrow, k, mvalid);
-            }
+            const int k = kt0 + min(u, cnt - 1) * WAVES;
+            raw[u] = load_tile(hi, lo, tile0 + k, lane);
+            xf[u] = load_x(xrow, k);
         }
-        for (int j0 = 0; j0 < cnt; j0 += D) {
+        // steady state, branch-free: D tiles per trip, each step refills the slot freed one step ago
+        int j0 = 0;
+        for (; j0 + 2 * D - 1 <= cnt; j0 += D) {
 #pragma unroll
             for (int u = 0; u < D; u++) {
-                const int j = j0 + u;
-                if (j < cnt) {
-                    if (j + D - 1 < cnt) {      // refill the slot consumed one step ago
-                        const int k = kt0 + (j + D - 1) * WAVES;
-                        raw[(u + D - 1) % D] = load_tile(hi, lo, tile0 + k, lane);
-                        xf[(u + D - 1) % D] = load_x(xrow, k, mvalid);
-                    }
-                    tile_mac(raw[u], xf[u], acc);
+                const int k = kt0 + (j0 + u + D - 1) * WAVES;
+                raw[(u + D - 1) % D] = load_tile(hi, lo, tile0 + k, lane);
+                xf[(u + D - 1) % D] = load_x(xrow, k);
+                tile_mac(raw[u], xf[u], acc);
+            }
+        }
+        // drain: the remaining (< 2D-1) tiles, refilling only while tiles are left
+#pragma unroll
+        for (int v = 0; v < 2 * D - 2; v++) {
+            const int j = j0 + v;
+            if (j < cnt) {
+                if (j + D - 1 < cnt) {
+                    const int k = kt0 + (j + D - 1) * WAVES;
+                    raw[(v + D - 1) % D] = load_tile(hi, lo, tile0 + k, lane);
+                    xf[(v + D - 1) % D] = load_x(xrow, k);
                 }
+                tile_mac(raw[v % D], xf[v % D], acc);
             }
         }
     }
