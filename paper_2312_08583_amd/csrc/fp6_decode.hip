@@ -120,8 +120,18 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
         if (!arrive_last(&counters[nb], (uint32_t)split_k)) return;
         if (tid < 256) {
             sum = float4v{0.f, 0.f, 0.f, 0.f};
-            for (int ss = 0; ss < split_k; ss++)
-                sum += load_partial(partial_window(partials + ((size_t)ss * nblocks + nb) * 256, 4096), tid);
+            // four slices in flight at a time; the additions stay in slice order
+            for (int ss = 0; ss < split_k; ss += 4) {
+                float4v v[4];
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    const int sl = min(ss + u, split_k - 1);
+                    v[u] = load_partial(partial_window(partials + ((size_t)sl * nblocks + nb) * 256, 4096), tid);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; u++)
+                    if (ss + u < split_k) sum += v[u];
+            }
         }
     }
 
