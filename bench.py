@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fp16-baseline", action="store_true")
     ap.add_argument("--legs", default="1,512", help="comma-separated M values to time")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 1 GiB device copy (calibrates the HBM byte counters of a profiler run)")
     return ap.parse_args()
 
 
@@ -106,6 +108,14 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / steps      # ms per pass
 
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     legs = [int(m) for m in args.legs.split(",")]
     res = {}
     for M in legs:
@@ -164,6 +174,16 @@ def main():
                    sample="layer 0 of the stack (7 linears, %.0f M weights) at M=1, oracle fp6o_linear, best of 3; "
                           "oracle quantization of the sample not timed" % (wsample / 1e6))
 
+    # HBM bytes per step from the committed counter summary (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)
+    traffic = {}
+    try:
+        for line in open(os.path.join(ROOT, "profiles", "bench_cfg5_hbm_traffic.txt")):
+            if line.startswith("TRAFFIC_BYTES_PER_STEP_M"):
+                k, v = line.strip().split("=")
+                traffic[int(k.rsplit("M", 1)[1])] = int(v) * layers // 48
+    except OSError:
+        pass
+
     lead = res[legs[0]]
     out = {
         "metric": "fp6_linear achieved HBM GB/s (M=1) and TFLOP/s (M=512) vs roofline, 1 MI355X",
@@ -177,11 +197,11 @@ def main():
                                "M=%d, %.2f G weights per step" % (WORKLOAD, layers, legs[0], weights_per_pass / 1e9),
                    "launches_per_step": launches, "build_seconds": round(build_s, 1)},
         "roofline": ({"bound": "hbm", "achieved": lead["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                      "frac": lead["gbs"] / HBM_PEAK_GBS, "traffic": None,
+                      "frac": lead["gbs"] / HBM_PEAK_GBS, "traffic": traffic.get(legs[0]),
                       "kernel": "decode_kernel (M<=16), all %d launches of a step" % launches}
                      if legs[0] <= 118 else
                      {"bound": "mfma", "achieved": lead["tflops"], "peak": MFMA_FP16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                      "frac": lead["tflops"] / MFMA_FP16_PEAK_TFLOPS, "traffic": None,
+                      "frac": lead["tflops"] / MFMA_FP16_PEAK_TFLOPS, "traffic": traffic.get(legs[0]),
                       "kernel": "gemm_kernel, all %d launches of a step" % launches}),
         "cpu_baseline": cpu,
     }
@@ -189,7 +209,7 @@ def main():
         r = res[512]
         out["m512"] = {"value": r["tflops"], "unit": "TFLOP/s", "ms_per_step": r["ms_per_step"],
                        "roofline": {"bound": "mfma", "achieved": r["tflops"], "peak": MFMA_FP16_PEAK_TFLOPS,
-                                    "unit": "TFLOP/s", "frac": r["tflops"] / MFMA_FP16_PEAK_TFLOPS, "traffic": None,
+                                    "unit": "TFLOP/s", "frac": r["tflops"] / MFMA_FP16_PEAK_TFLOPS, "traffic": traffic.get(512),
                                     "kernel": "gemm_kernel (block_m 128), all %d launches of a step" % launches}}
     if fp16 is not None:
         out["fp16_dense_baseline"] = {"kind": "torch.matmul (hipBLASLt) on the dequantized fp16 weights, same stack",
