@@ -12,7 +12,7 @@ from typing import Optional, Tuple
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libfp6_linear.so")
+LIB_PATH = os.environ.get("FP6_LINEAR_LIB", os.path.join(_HERE, "libfp6_linear.so"))   # override: tuning builds
 
 FP6_TILE = 64
 FP6_OK = 0

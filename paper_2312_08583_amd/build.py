@@ -15,20 +15,21 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
          "-Wall", "-Wno-unused-function"]
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
-    subprocess.run(["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj], check=True)
-    return obj
-
-
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, extra_flags=(), lib: str = LIB, tag: str = "") -> str:
+    """Compile every source and link `lib`.  extra_flags / tag are for tuning builds (-D switches)."""
     os.makedirs(OBJ, exist_ok=True)
+
+    def _compile(src: str) -> str:
+        obj = os.path.join(OBJ, os.path.splitext(src)[0] + tag + ".o")
+        subprocess.run(["hipcc", *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj], check=True)
+        return obj
+
     with ThreadPoolExecutor(max_workers=4) as ex:
         objs = list(ex.map(_compile, SOURCES))
-    subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
+    subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs], check=True)
     if verbose:
-        print("built", LIB)
-    return LIB
+        print("built", lib)
+    return lib
 
 
 if __name__ == "__main__":

@@ -52,16 +52,40 @@ bool make_plan(int64_t M, int64_t N, int64_t K, int variant, int split_k, Linear
         // up to 3 workgroups per compute unit are resident; at least two tiles per wavefront
         p.split_k = split_k ? split_k : pick_split(nblocks, ktiles, 768, 2 * p.waves);
     } else {
-        if (hint_waves || hint_depth || (hint_bm && hint_bm != 32 && hint_bm != 64 && hint_bm != 128)) return false;
+        if ((hint_waves && hint_waves != 4 && hint_waves != 8) || hint_depth ||
+            (hint_bm && hint_bm != 32 && hint_bm != 64 && hint_bm != 128))
+            return false;
         if (M * K * 2 >= ((int64_t)1 << 32)) return false;   // X is addressed with 32-bit lane offsets
-        p.block_m = hint_bm ? hint_bm : (M <= 32 ? 32 : (M <= 64 ? 64 : 128));
-        p.waves = 8;
+        p.waves = hint_waves ? hint_waves : 8;
+        // Pick rows per workgroup and the number of K-slices with a small cost model (microseconds,
+        // constants measured on MI355X): one workgroup per compute unit is resident, so the launch
+        // runs in ceil(workgroups/256) rounds; a round costs its k tiles at the per-tile time of the
+        // block size (or of the HBM stream, whichever is longer) plus a fixed part that grows with
+        // the number of slices the last workgroup of a tile has to add up.
+        double best_cost = 0.0;
+        for (int bm = 32; bm <= 128; bm *= 2) {
+            if (hint_bm ? bm != hint_bm : (bm > 32 && bm / 2 >= M)) continue;
+            const int64_t mblk = (M + bm - 1) / bm, t = mblk * ((nblocks + 7) / 8);
+            const double step = bm == 128 ? 1.47 : (bm == 64 ? 1.0 : 0.8);
+            const double slice = bm == 128 ? 8.0 : (bm == 64 ? 2.5 : 1.5);
+            for (int64_t d = 1; d <= ktiles && d <= 64; d++) {
+                if (ktiles % d || (split_k && d != split_k)) continue;
+                if (d > 1 && t > kMaxCounters) break;
+                const int64_t wgs = t * d, rounds = (wgs + 255) / 256, resident = wgs < 256 ? wgs : 256;
+                const double hbm_step = 24576.0 * (double)resident / (double)mblk / 5.5e6;
+                const double cost = (double)rounds * ((double)(ktiles / d) * (step > hbm_step ? step : hbm_step) + 6.0 +
+                                                      (d > 1 ? 3.0 + (double)d * slice : 0.0));
+                if (best_cost == 0.0 || cost < best_cost) {
+                    best_cost = cost;
+                    p.block_m = bm;
+                    p.split_k = (int)d;
+                }
+            }
+        }
+        if (best_cost == 0.0) return false;
         p.depth = p.block_m == 128 ? 3 : 4;
-        const int64_t mblk = (M + p.block_m - 1) / p.block_m, nblk = (nblocks + 7) / 8;
-        tiles = mblk * nblk;
+        tiles = ((M + p.block_m - 1) / p.block_m) * ((nblocks + 7) / 8);
         regs_per_tile = (int64_t)(p.block_m / 16) * 4 * 512;
-        // one workgroup (eight wavefronts) per compute unit is resident
-        p.split_k = split_k ? split_k : pick_split(tiles, ktiles, 256, 16);
     }
     if (p.split_k > 1) {
         if (tiles > kMaxCounters) {

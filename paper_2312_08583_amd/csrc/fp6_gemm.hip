@@ -1,34 +1,45 @@
 // Tiled kernel (any M) of the W6A16 linear layer for gfx950.
 //
-// A workgroup of eight wavefronts (two per SIMD) computes a BM x 512 block of Y.  The
-// wavefronts stand side by side along N (64 output channels each), so every packed
+// A workgroup computes a BM x 512 block of Y.  Its wavefronts stand side by side along
+// N, each owning WN 64-wide blocks of output channels (WN = 1: eight wavefronts, two per
+// SIMD; WN = 2: four wavefronts, one per SIMD, 128 x 128 results each).  Every packed
 // weight is fetched and padded to fp16 (bias shift, Section 5.2) by exactly one
-// wavefront of the workgroup and goes straight into MFMA operand registers - the
-// dequantized weight never exists in memory.  Only the activations are shared.
+// wavefront and goes straight into MFMA operand registers - the dequantized weight never
+// exists in memory.  Only the activations are shared.
 //
 // All global traffic of the main loop is asynchronous DMA into LDS (global_load_lds,
 // 16 bytes per lane, no register staging), into a ring of D stages per workgroup:
-//   - the BM x 64 slice of X for a k tile (read by all eight wavefronts as MFMA
-//     operands).  Rows are not padded; the 16-byte chunk c of row r is stored at chunk
-//     position c ^ (r & 7), which keeps the DMA writes and the 128-bit operand reads
-//     free of bank conflicts;
-//   - each wavefront's own 3 KB of packed planes for that k tile (lane-linear, exactly
-//     the order the planes have in memory).
+//   - the BM x 64 slice of X for a k tile (read by every wavefront as MFMA operands).
+//     Rows are not padded; the 16-byte chunk c of row r is stored at chunk position
+//     c ^ (r & 7), which keeps the DMA writes and the 128-bit operand reads free of bank
+//     conflicts;
+//   - each wavefront's own 3 KB of packed planes per block of output channels
+//     (lane-linear, exactly the order the planes have in memory).
 // The DMA is issued from inline assembly and waited for with explicit s_waitcnt vmcnt:
 // every step issues the same number of loads per wavefront, so "at most (D-2) groups
 // still in flight" is a constant, and the compiler (which cannot see these loads) has
 // no reason to drain the queue.  One barrier per k tile publishes the landed stage and
-// frees the stage consumed in the previous step.  The row scale is applied once, after
-// the accumulation (Section 5.2).  K may be split over workgroups; the slices meet in
-// an fp32 workspace exactly as in the decode kernel.
+// frees the stage consumed in the previous step.
+//
+// What bounds the loop is LDS bandwidth: every wavefront reads the whole X slice, so a
+// step moves (wavefronts x BM x 128 B) + planes through a 128 B/clk port.  With eight
+// wavefronts at BM = 128 that is 152 KB per 2048 MFMA cycles - the port is saturated
+// by data movement alone; four wavefronts with twice the channels each halve it.
+//
+// The row scale is applied once, after the accumulation (Section 5.2).  K may be split
+// over workgroups; the slices meet in an fp32 workspace exactly as in the decode kernel.
 #include "fp6_common.hpp"
 #include "fp6_internal.hpp"
 #include "fp6_reduce.hpp"
 
+#ifndef FP6_GEMM_HINTS
+#define FP6_GEMM_HINTS 1
+#endif
+
 namespace fp6 {
 
-constexpr int kGemmWaves = 8;
-constexpr int kWaveTileBytes = kHiTileBytes + kLoTileBytes;   // 3072: one wavefront's planes of one tile
+constexpr int kGemmBlocksN = 8;                               // 64-wide blocks of output channels per workgroup
+constexpr int kWaveTileBytes = kHiTileBytes + kLoTileBytes;   // 3072: the planes of one 64x64 tile
 
 // 16 bytes per lane from (base + lane_offset) to LDS address lds + 16 * lane (lds is wave-uniform).
 // M0 carries the LDS address; nothing else in these kernels uses M0 (gfx9 DS instructions do not),
@@ -48,34 +59,54 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
-template <int BM, int D>
-__global__ __launch_bounds__(kGemmWaves * 64) void gemm_kernel(
+template <int BM, int D, int WN>
+__global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
     const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
     const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
     float4v* __restrict__ partials, uint32_t* __restrict__ counters, int split_k)
 {
+    constexpr int WAVES = kGemmBlocksN / WN;
+    constexpr int THREADS = WAVES * 64;
     constexpr int MT = BM / 16;                         // 16-row blocks of X per workgroup
+    constexpr int NT = 4 * WN;                          // 16-channel blocks per wavefront
     constexpr int XG = BM / 8;                          // 8-row groups (1 KB of DMA each) per stage
-    constexpr int XL = XG >= kGemmWaves ? XG / kGemmWaves : 1;   // X groups moved per wavefront and k tile
-    constexpr int kLoads = XL + 3;                      // DMA instructions per wavefront and k tile
+    constexpr int XL = XG >= WAVES ? XG / WAVES : 1;    // X groups moved per wavefront and k tile
+    constexpr int kLoads = XL + 3 * WN;                 // DMA instructions per wavefront and k tile
     constexpr int kXBytes = BM * kTile * 2;
-    constexpr int kStageBytes = kXBytes + kGemmWaves * kWaveTileBytes;
+    constexpr int kStageBytes = kXBytes + kGemmBlocksN * kWaveTileBytes;
+    constexpr int kTileRegs = MT * NT * THREADS;        // float4 per output tile
     __shared__ __align__(16) unsigned char smem[D * kStageBytes];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ktiles = K / kTile, nblocks = N / kTile;
     const int mblk = (M + BM - 1) / BM;
-    int id = blockIdx.x;
-    const int s = id % split_k;
-    id /= split_k;
-    const int mb = id % mblk, nbw = id / mblk;
+    const int nblk = (nblocks + kGemmBlocksN - 1) / kGemmBlocksN;
+    // Workgroups are dealt round-robin to the eight compute dies, each with its own L2.  The
+    // workgroups that read the same planes (same block of weights and K-slice, different rows of
+    // X) get ids that are congruent mod 8, so they run on one die and the planes are fetched
+    // into one L2 once.  The (weight block, K-slice) pairs themselves are spread over all dies.
+    // With at least eight weight blocks it is the blocks that are dealt to the dies (all K-slices
+    // of a block on one die); with fewer, the pairs are, so that no die stays idle.
+    const int xcd = blockIdx.x & 7;
+    int id = blockIdx.x >> 3;
+    const int mb = id % mblk;
+    id /= mblk;
+    int nbw, s;
+    if (nblk >= 8) {
+        s = id % split_k;
+        nbw = (id / split_k) * 8 + xcd;
+        if (nbw >= nblk) return;             // the grid is padded to a multiple of eight blocks
+    } else {
+        const int pair = id * 8 + xcd;
+        if (pair >= nblk * split_k) return;  // ... or of eight pairs
+        nbw = pair / split_k;
+        s = pair % split_k;
+    }
     const int kt_per = ktiles / split_k;
     const int kt_begin = s * kt_per, kt_end = kt_begin + kt_per;
     const int m0 = mb * BM;
-    const int nb = nbw * kGemmWaves + wave;
-    const bool wvalid = nb < nblocks;
-    const size_t tile0 = (size_t)(wvalid ? nb : 0) * ktiles;
+    const int nb0 = nbw * kGemmBlocksN + wave * WN;     // first block of output channels of this wavefront
     const int i = lane & 15, g = lane >> 4;
     const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
@@ -91,7 +122,11 @@ __global__ __launch_bounds__(kGemmWaves * 64) void gemm_kernel(
         xlds[p] = j * 1024;
     }
     const uint32_t wlane = lane * 16;
-    const uint32_t wlds = kXBytes + wave * kWaveTileBytes;
+    const uint32_t wlds = kXBytes + wave * WN * kWaveTileBytes;
+    // blocks of channels past N are computed on the last valid block and dropped
+    size_t tile0[WN];
+#pragma unroll
+    for (int c = 0; c < WN; c++) tile0[c] = (size_t)min(nb0 + c, nblocks - 1) * ktiles;
 
     // kLoads DMA instructions per call, always
     auto issue = [&](int kt, int stage) {
@@ -99,49 +134,74 @@ __global__ __launch_bounds__(kGemmWaves * 64) void gemm_kernel(
         const unsigned char* xb = reinterpret_cast<const unsigned char*>(X) + (size_t)kt * (kTile * 2);
 #pragma unroll
         for (int p = 0; p < XL; p++) dma16(xb, xlane[p], sb + xlds[p]);
-        const unsigned char* hb = reinterpret_cast<const unsigned char*>(hi) + (tile0 + kt) * kHiTileBytes;
-        const unsigned char* lb = reinterpret_cast<const unsigned char*>(lo) + (tile0 + kt) * kLoTileBytes;
-        dma16(hb, wlane, sb + wlds);
-        dma16(hb + 1024, wlane, sb + wlds + 1024);
-        dma16(lb, wlane, sb + wlds + 2048);
+#pragma unroll
+        for (int c = 0; c < WN; c++) {
+            const unsigned char* hb = reinterpret_cast<const unsigned char*>(hi) + (tile0[c] + kt) * kHiTileBytes;
+            const unsigned char* lb = reinterpret_cast<const unsigned char*>(lo) + (tile0[c] + kt) * kLoTileBytes;
+            dma16(hb, wlane, sb + wlds + c * kWaveTileBytes);
+            dma16(hb + 1024, wlane, sb + wlds + c * kWaveTileBytes + 1024);
+            dma16(lb, wlane, sb + wlds + c * kWaveTileBytes + 2048);
+        }
     };
 
     // operand reads: row r = 16a + i, chunk 4q + g, at position (4q + g) ^ (i & 7)
     const int xoff0 = i * (kTile * 2) + ((g ^ (i & 7)) * 16);
     const int xoff1 = i * (kTile * 2) + (((4 + g) ^ (i & 7)) * 16);
 
-    float4v acc[MT][4];
+    float4v acc[MT][NT];
 #pragma unroll
     for (int a = 0; a < MT; a++)
 #pragma unroll
-        for (int t = 0; t < 4; t++) acc[a][t] = float4v{0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < NT; t++) acc[a][t] = float4v{0.f, 0.f, 0.f, 0.f};
 
 #pragma unroll
     for (int u = 0; u < D - 1; u++) issue(min(kt_begin + u, kt_end - 1), u);
 
-    // one k tile: its DMA was issued D-1 steps ago; D-2 younger groups may stay in flight
+    // One k tile.  Its DMA was issued D-1 steps ago; D-2 younger groups may stay in flight.  The
+    // stage number u is a compile-time constant (the loop below is unrolled by D), so every LDS
+    // address is a register plus an immediate - a ring indexed at run time measured 10-20% slower.
     auto step = [&](int kt, int u) {
         wait_vmcnt<(D - 2) * kLoads>();
         __syncthreads();          // everyone's DMA landed; everyone is done with the stage refilled next
         issue(min(kt + D - 1, kt_end - 1), (u + D - 1) % D);
         const unsigned char* st = smem + u * kStageBytes;
-        TileRaw raw;
-        raw.hi0 = *reinterpret_cast<const u32x4*>(st + wlds + wlane);
-        raw.hi1 = *reinterpret_cast<const u32x4*>(st + wlds + 1024 + wlane);
-        raw.lo = *reinterpret_cast<const u32x4*>(st + wlds + 2048 + wlane);
+        const unsigned char* wt = st + wlds;
+        TileRaw raw[WN];
+#pragma unroll
+        for (int c = 0; c < WN; c++) {
+            raw[c].hi0 = *reinterpret_cast<const u32x4*>(wt + c * kWaveTileBytes + wlane);
+            raw[c].hi1 = *reinterpret_cast<const u32x4*>(wt + c * kWaveTileBytes + 1024 + wlane);
+            raw[c].lo = *reinterpret_cast<const u32x4*>(wt + c * kWaveTileBytes + 2048 + wlane);
+        }
 #pragma unroll
         for (int q = 0; q < 2; q++) {
             half8 xf[MT];
 #pragma unroll
-            for (int a = 0; a < MT; a++)
+            for (int a = 0; a < MT; a++) {
                 xf[a] = *reinterpret_cast<const half8*>(st + a * 16 * (kTile * 2) + (q ? xoff1 : xoff0));
+            }
 #pragma unroll
-            for (int t = 0; t < 4; t++) {
-                half8 w = unpack_tile_fragment(raw, 2 * t + q);
+            for (int t = 0; t < NT; t++) {
+                half8 w = unpack_tile_fragment(raw[t / 4], 2 * (t % 4) + q);
 #pragma unroll
                 for (int a = 0; a < MT; a++) acc[a][t] = mfma16x16x32(w, xf[a], acc[a][t]);
             }
         }
+        // Issue order.  The wavefronts of a SIMD leave the barrier together, so they cannot hide
+        // each other's unpack work; instead, after the first fragment, every MFMA (16 cycles in the
+        // matrix pipe) is followed by two of the unpack VALU operations (8 cycles of issue, in its
+        // shadow), and the LDS operand reads of the second k block are spread over the MFMAs of
+        // the first.
+#if FP6_GEMM_HINTS
+        __builtin_amdgcn_sched_group_barrier(0x100, 3 * WN + MT, 0);     // planes + operands of k block 0
+        __builtin_amdgcn_sched_group_barrier(0x002, 15, 0);              // first fragment
+#pragma unroll
+        for (int n = 0; n < 2 * NT * MT; n++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+            if (n % 2 == 0 && n >= NT * MT - 2 * MT && n < NT * MT) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+#endif
     };
 
     int kt = kt_begin;
@@ -156,68 +216,90 @@ __global__ __launch_bounds__(kGemmWaves * 64) void gemm_kernel(
     wait_vmcnt<0>();     // the over-fetched ring slots must land before LDS is given back
     __syncthreads();
 
+    // Everything below is addressed through a copy of the thread index that the compiler cannot
+    // see through, so that none of its address arithmetic is hoisted above the main loop, where it
+    // would take registers the loop needs (and a spilled value reloaded inside the loop makes the
+    // compiler drain the DMA queue).
+    int tid2 = tid;
+    asm volatile("" : "+v"(tid2));
+    const int i2 = tid2 & 15, g2 = (tid2 >> 4) & 3;
+
     // ---- K-slices of other workgroups
     if (split_k > 1) {
-        const int tile = nbw * mblk + mb, ntiles = gridDim.x / split_k;
-        constexpr int kTileRegs = MT * 4 * kGemmWaves * 64;      // float4 per output tile
-        if (wvalid) {
+        const int tile = nbw * mblk + mb, ntiles = mblk * nblk;
+        {
             __amdgpu_buffer_rsrc_t win = partial_window(partials + ((size_t)s * ntiles + tile) * kTileRegs, kTileRegs * 16);
 #pragma unroll
             for (int a = 0; a < MT; a++)
 #pragma unroll
-                for (int t = 0; t < 4; t++) store_partial(win, (a * 4 + t) * (kGemmWaves * 64) + tid, acc[a][t]);
+                for (int t = 0; t < NT; t++) store_partial(win, (a * NT + t) * THREADS + tid2, acc[a][t]);
         }
         if (!arrive_last(&counters[tile], (uint32_t)split_k)) return;
-        if (wvalid) {
 #pragma unroll
-            for (int a = 0; a < MT; a++)
+        for (int a = 0; a < MT; a++)
 #pragma unroll
-                for (int t = 0; t < 4; t++) acc[a][t] = float4v{0.f, 0.f, 0.f, 0.f};
-            for (int ss = 0; ss < split_k; ss++) {
-                __amdgpu_buffer_rsrc_t win = partial_window(partials + ((size_t)ss * ntiles + tile) * kTileRegs, kTileRegs * 16);
+            for (int t = 0; t < NT; t++) acc[a][t] = float4v{0.f, 0.f, 0.f, 0.f};
+        for (int ss = 0; ss < split_k; ss++) {
+            __amdgpu_buffer_rsrc_t win = partial_window(partials + ((size_t)ss * ntiles + tile) * kTileRegs, kTileRegs * 16);
+            // sixteen 16-byte loads in flight at a time: more would need registers the main loop
+            // cannot spare
+            constexpr int AG = (MT * NT < 16) ? MT : 16 / NT;
 #pragma unroll
-                for (int a = 0; a < MT; a++)
+            for (int a0 = 0; a0 < MT; a0 += AG) {
+                float4v v[AG][NT];
 #pragma unroll
-                    for (int t = 0; t < 4; t++) acc[a][t] += load_partial(win, (a * 4 + t) * (kGemmWaves * 64) + tid);
+                for (int a = 0; a < AG; a++)
+#pragma unroll
+                    for (int t = 0; t < NT; t++) v[a][t] = load_partial(win, ((a0 + a) * NT + t) * THREADS + tid2);
+#pragma unroll
+                for (int a = 0; a < AG; a++)
+#pragma unroll
+                    for (int t = 0; t < NT; t++) acc[a0 + a][t] += v[a][t];
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
 
-    // ---- epilogue: lane holds rows n = 16t + 4g + r of column m = 16a + i
-    if (!wvalid) return;
-    float sc[4][4];
+    // ---- epilogue: lane holds channels n = 16t + 4g + r of row m = 16a + i  (i2, g2 = i, g)
 #pragma unroll
-    for (int t = 0; t < 4; t++) {
-        const half4 h = *reinterpret_cast<const half4*>(scales + (size_t)nb * kTile + t * 16 + g * 4);
+    for (int c = 0; c < WN; c++) {
+        const int nb = nb0 + c;
+        if (nb >= nblocks) break;
+        float sc[4][4];
 #pragma unroll
-        for (int r = 0; r < 4; r++) sc[t][r] = (float)h[r] * 4096.0f;
-    }
+        for (int t = 0; t < 4; t++) {
+            const half4 h = *reinterpret_cast<const half4*>(scales + (size_t)nb * kTile + t * 16 + g2 * 4);
 #pragma unroll
-    for (int a = 0; a < MT; a++) {
-        const int m = m0 + a * 16 + i;
-        if (m < M) {
+            for (int r = 0; r < 4; r++) sc[t][r] = (float)h[r] * 4096.0f;
+        }
 #pragma unroll
-            for (int t = 0; t < 4; t++) {
-                half4 y;
+        for (int a = 0; a < MT; a++) {
+            const int m = m0 + a * 16 + i2;
+            if (m < M) {
 #pragma unroll
-                for (int r = 0; r < 4; r++) y[r] = (_Float16)(acc[a][t][r] * sc[t][r]);
-                *reinterpret_cast<half4*>(Y + (size_t)m * N + (size_t)nb * kTile + t * 16 + g * 4) = y;
+                for (int t = 0; t < 4; t++) {
+                    half4 y;
+#pragma unroll
+                    for (int r = 0; r < 4; r++) y[r] = (_Float16)(acc[a][c * 4 + t][r] * sc[t][r]);
+                    *reinterpret_cast<half4*>(Y + (size_t)m * N + (size_t)nb * kTile + t * 16 + g2 * 4) = y;
+                }
             }
         }
     }
 }
 
-template <int BM, int D>
+template <int BM, int D, int WN>
 static hipError_t launch_gemm_t(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
                                 const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                                 hipStream_t stream)
 {
     uint32_t* counters = reinterpret_cast<uint32_t*>(workspace);
     float4v* partials = reinterpret_cast<float4v*>(reinterpret_cast<char*>(workspace) + kCounterBytes);
-    const int64_t mblk = (M + BM - 1) / BM, nblk = (N / kTile + kGemmWaves - 1) / kGemmWaves;
-    const unsigned grid = (unsigned)(mblk * nblk * p.split_k);
-    hipLaunchKernelGGL((gemm_kernel<BM, D>), dim3(grid), dim3(kGemmWaves * 64), 0, stream, X, (int)M, (const u32x4*)hi,
-                       (const u32x4*)lo, scales, (int)N, (int)K, Y, partials, counters, p.split_k);
+    const int64_t mblk = (M + BM - 1) / BM, nblk = (N / kTile + kGemmBlocksN - 1) / kGemmBlocksN;
+    const unsigned grid = (unsigned)(nblk >= 8 ? mblk * ((nblk + 7) / 8 * 8) * p.split_k
+                                               : mblk * ((nblk * p.split_k + 7) / 8 * 8));   // padded: see the id mapping
+    hipLaunchKernelGGL((gemm_kernel<BM, D, WN>), dim3(grid), dim3(kGemmBlocksN / WN * 64), 0, stream, X, (int)M,
+                       (const u32x4*)hi, (const u32x4*)lo, scales, (int)N, (int)K, Y, partials, counters, p.split_k);
     return hipGetLastError();
 }
 
@@ -225,10 +307,13 @@ hipError_t launch_gemm(const LinearPlan& p, const uint16_t* X, int64_t M, const 
                        const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                        hipStream_t stream)
 {
-    switch (p.block_m) {
-        case 32: return launch_gemm_t<32, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-        case 64: return launch_gemm_t<64, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-        default: return launch_gemm_t<128, 3>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+    switch (p.block_m * 10 + p.waves) {
+        case 328: return launch_gemm_t<32, 4, 1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        case 324: return launch_gemm_t<32, 4, 2>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        case 648: return launch_gemm_t<64, 4, 1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        case 644: return launch_gemm_t<64, 4, 2>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        case 1288: return launch_gemm_t<128, 3, 1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        default: return launch_gemm_t<128, 3, 2>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     }
 }
 
