@@ -121,14 +121,16 @@ int fp6_dequantize(const void *hi_plane, const void *lo_plane, const uint16_t *s
                    int64_t N, int64_t K, uint16_t *W_hat, void *stream);
 
 /*
- * Bytes of device workspace fp6_linear may need for this shape (0 is possible).  The
- * workspace holds fp32 partial sums of K-slices and one arrival counter per output
- * tile.  CONTRACT: its first FP6_WORKSPACE_COUNTER_BYTES bytes must be zero before the
- * first call that uses it; every call leaves them zero again, so one buffer can be
- * reused by successive calls on the same stream.  Calls that share a workspace must
- * not overlap in time.
+ * Bytes of device workspace fp6_linear may need for this shape (0 is possible).  When K
+ * is cut into slices handled by different workgroups, the workspace is where the slices'
+ * fp32 partial sums meet: small ones pairwise in 64-bit slots, large ones through a
+ * buffer guarded by one arrival counter per output tile.  CONTRACT: the first
+ * FP6_WORKSPACE_ZERO_BYTES bytes (counters and slots) must be zero before the first call
+ * that uses the workspace; every call leaves them zero again, so one buffer can be reused
+ * by successive calls on the same stream, whatever their shapes.  Calls that share a
+ * workspace must not overlap in time.
  */
-#define FP6_WORKSPACE_COUNTER_BYTES 16384
+#define FP6_WORKSPACE_ZERO_BYTES 4259840
 size_t fp6_linear_workspace_bytes(int64_t M, int64_t N, int64_t K);
 
 /*
@@ -155,11 +157,14 @@ int fp6_linear(const uint16_t *X, int64_t M, const void *hi_plane, const void *l
  *                       wavefront owning 128 output channels; 8 = two per SIMD, 64 channels each)
  *   FP6_HINT_DEPTH(d)   tiles in the per-wavefront prefetch ring, decode family: 2..4
  *   FP6_HINT_BLOCK_M(b) rows of X per workgroup, gemm family: 32, 64 or 128
+ *   FP6_HINT_MEET(x)    decode family with split_k > 1: 1 = K-slices meet at an arrival counter,
+ *                       2 = pairwise in slots (needs split_k * (N/64) * 256 * M <= 2^22)
  * An unsupported combination returns FP6_ERR_VARIANT.
  */
 #define FP6_HINT_WAVES(w) ((int)(w) << 8)
 #define FP6_HINT_DEPTH(d) ((int)(d) << 12)
 #define FP6_HINT_BLOCK_M(b) (((int)(b) / 16) << 16)
+#define FP6_HINT_MEET(x) ((int)(x) << 20)
 size_t fp6_linear_variant_workspace_bytes(int64_t M, int64_t N, int64_t K, int variant, int split_k);
 int fp6_linear_variant(const uint16_t *X, int64_t M, const void *hi_plane, const void *lo_plane,
                        const uint16_t *scales, int64_t N, int64_t K, uint16_t *Y,

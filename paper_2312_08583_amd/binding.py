@@ -17,7 +17,25 @@ LIB_PATH = os.environ.get("FP6_LINEAR_LIB", os.path.join(_HERE, "libfp6_linear.s
 FP6_TILE = 64
 FP6_OK = 0
 FP6_VARIANT_AUTO, FP6_VARIANT_DECODE, FP6_VARIANT_GEMM = 0, 1, 2
-FP6_WORKSPACE_COUNTER_BYTES = 16384
+FP6_WORKSPACE_ZERO_BYTES = 4259840
+
+
+# tuning hints carried in the upper bits of `variant` (same macros as the header)
+def FP6_HINT_WAVES(w: int) -> int:
+    return int(w) << 8
+
+
+def FP6_HINT_DEPTH(d: int) -> int:
+    return int(d) << 12
+
+
+def FP6_HINT_BLOCK_M(b: int) -> int:
+    return (int(b) // 16) << 16
+
+
+def FP6_HINT_MEET(x: int) -> int:
+    return int(x) << 20
+
 
 EXPORTS = ["fp6_layout_version", "fp6_status_string", "fp6_packed_sizes", "fp6_quantize_pack",
            "fp6_unpack_codes", "fp6_dequantize", "fp6_linear_workspace_bytes", "fp6_linear",

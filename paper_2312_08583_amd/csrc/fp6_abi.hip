@@ -31,7 +31,8 @@ bool make_plan(int64_t M, int64_t N, int64_t K, int variant, int split_k, Linear
 {
     const int64_t ktiles = K / FP6_TILE, nblocks = N / FP6_TILE;
     // tuning hints ride in the upper bits of `variant`; 0 = automatic
-    const int hint_waves = (variant >> 8) & 0xF, hint_depth = (variant >> 12) & 0xF, hint_bm = ((variant >> 16) & 0xFF) * 16;
+    const int hint_waves = (variant >> 8) & 0xF, hint_depth = (variant >> 12) & 0xF, hint_bm = ((variant >> 16) & 0xF) * 16,
+              hint_meet = (variant >> 20) & 0x3;
     variant &= 0xFF;
     if (variant == FP6_VARIANT_AUTO) variant = (M <= 16) ? FP6_VARIANT_DECODE : FP6_VARIANT_GEMM;
     if (variant != FP6_VARIANT_DECODE && variant != FP6_VARIANT_GEMM) return false;
@@ -42,7 +43,8 @@ bool make_plan(int64_t M, int64_t N, int64_t K, int variant, int split_k, Linear
     p.variant = variant;
     int64_t tiles, regs_per_tile;
     if (variant == FP6_VARIANT_DECODE) {
-        if ((hint_waves && hint_waves != 4 && hint_waves != 8) || (hint_depth && (hint_depth < 2 || hint_depth > 4)) || hint_bm)
+        if ((hint_waves && hint_waves != 4 && hint_waves != 8) || (hint_depth && (hint_depth < 2 || hint_depth > 4)) || hint_bm ||
+            hint_meet > 2)
             return false;
         p.block_m = 16;
         p.waves = hint_waves ? hint_waves : 4;
@@ -52,7 +54,7 @@ bool make_plan(int64_t M, int64_t N, int64_t K, int variant, int split_k, Linear
         // up to 3 workgroups per compute unit are resident; at least two tiles per wavefront
         p.split_k = split_k ? split_k : pick_split(nblocks, ktiles, 768, 2 * p.waves);
     } else {
-        if ((hint_waves && hint_waves != 4 && hint_waves != 8) || hint_depth ||
+        if ((hint_waves && hint_waves != 4 && hint_waves != 8) || hint_depth || hint_meet ||
             (hint_bm && hint_bm != 32 && hint_bm != 64 && hint_bm != 128))
             return false;
         if (M * K * 2 >= ((int64_t)1 << 32)) return false;   // X is addressed with 32-bit lane offsets
@@ -94,14 +96,21 @@ bool make_plan(int64_t M, int64_t N, int64_t K, int variant, int split_k, Linear
         }
     }
     if (p.split_k > 1) {
-        p.counters = (int)tiles;
-        p.partial_bytes = (size_t)p.split_k * (size_t)tiles * (size_t)regs_per_tile * 16u;
+        // Decode: two slices meet pairwise (one memory round trip instead of three) if the tree nodes,
+        // 256 * M bytes each, fit the slot region; deeper trees measured slower than the counter.
+        const bool fits = M <= 16 && (int64_t)p.split_k * tiles * 256 * M <= (int64_t)kSlotBytes;
+        if (variant == FP6_VARIANT_DECODE && hint_meet == 2 && !fits) return false;
+        p.pairwise = variant == FP6_VARIANT_DECODE && fits && (hint_meet ? hint_meet == 2 : p.split_k == 2);
+        if (!p.pairwise) {
+            p.counters = (int)tiles;
+            p.partial_bytes = (size_t)p.split_k * (size_t)tiles * (size_t)regs_per_tile * 16u;
+        }
     }
     *plan = p;
     return true;
 }
 
-static size_t plan_workspace(const LinearPlan& p) { return p.split_k > 1 ? kCounterBytes + p.partial_bytes : 0; }
+static size_t plan_workspace(const LinearPlan& p) { return p.split_k > 1 ? kZeroBytes + p.partial_bytes : 0; }
 
 }  // namespace fp6
 

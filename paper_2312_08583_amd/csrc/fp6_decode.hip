@@ -8,9 +8,10 @@
 // and feeds eight v_mfma_f32_16x16x32_f16 (weights = A, the <=16 rows of X = B, padded
 // with zero columns).  X is tiny and L2-resident, so each wavefront reads its 16-byte
 // operand slices of X directly.  Partial sums of the wavefronts are added in LDS; if K
-// is also split over workgroups the slices meet in an fp32 workspace and the workgroup
-// that arrives last adds them in slice order (deterministic) and applies the epilogue
-// Y = fp16(acc * S_n * 2^12) - the row scale after the accumulation (Section 5.2).
+// is also split over workgroups the slices meet in the workspace - two slices pairwise in
+// a slot, more at an arrival counter, where the workgroup that arrives last adds them in
+// slice order (both deterministic) - and whoever holds the total applies the epilogue
+// Y = fp16(acc * S_n * 2^12), the row scale after the accumulation (Section 5.2).
 #include "fp6_common.hpp"
 #include "fp6_internal.hpp"
 #include "fp6_reduce.hpp"
@@ -47,7 +48,8 @@ template <int WAVES, int D>
 __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
     const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
-    float4v* __restrict__ partials, uint32_t* __restrict__ counters, int split_k)
+    float4v* __restrict__ partials, uint32_t* __restrict__ counters, unsigned long long* __restrict__ slots,
+    int split_k, int pairwise)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int ktiles = K / kTile;
@@ -59,6 +61,10 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     const uint16_t* xrow = X + (size_t)min(m, M - 1) * K + g * 8;
     const size_t tile0 = (size_t)nb * ktiles;
 
+    // row scales of the four channels this thread will store (fetched early: the epilogue is latency-bound)
+    half4 sc = half4{0, 0, 0, 0};
+    if ((int)threadIdx.x < 16 * M) sc = *reinterpret_cast<const half4*>(scales + nb * kTile + (threadIdx.x & 15) * 4);
+
     float4v acc[4];
 #pragma unroll
     for (int t = 0; t < 4; t++) acc[t] = float4v{0.f, 0.f, 0.f, 0.f};
@@ -69,6 +75,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     if (cnt > 0) {
         TileRaw raw[D];
         XFrag xf[D];
+
         // prologue: tiles 0 .. D-2 (clamped: a short wavefront re-reads its last tile)
 #pragma unroll
         for (int u = 0; u < D - 1; u++) {
@@ -103,49 +110,68 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     }
 
     // ---- add the wavefronts' partial sums in LDS
+    // MFMA result layout: lane 16g + m of accumulator t holds channels 16t + 4g + r (r = 0..3)
+    // of column m.  Thread m*16 + (4t + g) takes that value, so the threads of the M valid
+    // columns come first and a column's 64 channels sit in 16 consecutive threads.
     __shared__ float4v red[WAVES][256];
 #pragma unroll
     for (int t = 0; t < 4; t++) red[wave][t * 64 + lane] = acc[t];
     __syncthreads();
     const int tid = threadIdx.x;
+    const bool active = tid < 16 * M;            // M <= 16, so at most 256 threads
+    const int mm = tid >> 4, n4 = tid & 15;
     float4v sum = float4v{0.f, 0.f, 0.f, 0.f};
-    if (tid < 256) {
+    if (active) {
+        const int src = (n4 >> 2) * 64 + (n4 & 3) * 16 + mm;
 #pragma unroll
-        for (int w = 0; w < WAVES; w++) sum += red[w][tid];
+        for (int w = 0; w < WAVES; w++) sum += red[w][src];
     }
 
-    // ---- add the K-slices of other workgroups (last arrival does it, in slice order)
-    if (split_k > 1) {
-        if (tid < 256) store_partial(partial_window(partials + ((size_t)s * nblocks + nb) * 256, 4096), tid, sum);
-        if (!arrive_last(&counters[nb], (uint32_t)split_k)) return;
-        if (tid < 256) {
+    // ---- add the K-slices of other workgroups
+    bool keep_lo = active, keep_hi = active;     // which halves of `sum` this thread finishes
+    if (split_k > 1 && pairwise) {
+        // pairwise meeting, two values per slot: thread tid owns slots 2*tid and 2*tid + 1 of a node
+        if (active) {
+            const size_t node = (size_t)32 * M;          // 64-bit slots per tree node
+            unsigned long long* mine = slots + (size_t)nb * split_k * node + tid * 2;
+            Pair p0{sum[0], sum[1]}, p1{sum[2], sum[3]};
+            keep_lo = meet_tree(mine, node, s, split_k, p0);
+            keep_hi = meet_tree(mine + 1, node, s, split_k, p1);
+            sum = float4v{p0.a, p0.b, p1.a, p1.b};
+        }
+    } else if (split_k > 1) {
+        // meeting at a counter: the last arrival adds all slices in slice order
+        if (active) store_partial(partial_window(partials + ((size_t)nb * split_k + s) * 256, 4096), tid, sum);
+        if (!arrive_last(&counters[nb * kCounterStride], (uint32_t)split_k)) return;
+        if (active) {
             sum = float4v{0.f, 0.f, 0.f, 0.f};
-            // four slices in flight at a time; the additions stay in slice order
-            for (int ss = 0; ss < split_k; ss += 4) {
-                float4v v[4];
+            // up to sixteen slices in flight at a time
+            for (int ss = 0; ss < split_k; ss += 16) {
+                float4v v[16];
 #pragma unroll
-                for (int u = 0; u < 4; u++) {
+                for (int u = 0; u < 16; u++) {
                     const int sl = min(ss + u, split_k - 1);
-                    v[u] = load_partial(partial_window(partials + ((size_t)sl * nblocks + nb) * 256, 4096), tid);
+                    v[u] = load_partial(partial_window(partials + ((size_t)nb * split_k + sl) * 256, 4096), tid);
                 }
 #pragma unroll
-                for (int u = 0; u < 4; u++)
+                for (int u = 0; u < 16; u++)
                     if (ss + u < split_k) sum += v[u];
             }
         }
     }
 
-    // ---- epilogue: thread (t, l) holds rows n = 16t + 4(l/16) + r of column m = l%16
-    if (tid < 256) {
-        const int t = tid >> 6, l = tid & 63;
-        const int mm = l & 15;
-        if (mm < M) {
-            const int n = nb * kTile + t * 16 + (l >> 4) * 4;
-            const half4 sc = *reinterpret_cast<const half4*>(scales + n);
-            half4 y;
+    // ---- epilogue: 16 consecutive threads store the 64 channels of one row of Y
+    if (keep_lo || keep_hi) {
+        half4 y;
 #pragma unroll
-            for (int r = 0; r < 4; r++) y[r] = (_Float16)(sum[r] * ((float)sc[r] * 4096.0f));
-            *reinterpret_cast<half4*>(Y + (size_t)mm * N + n) = y;
+        for (int r = 0; r < 4; r++) y[r] = (_Float16)(sum[r] * ((float)sc[r] * 4096.0f));
+        uint16_t* dst = Y + (size_t)mm * N + nb * kTile + n4 * 4;
+        if (keep_lo && keep_hi) {
+            *reinterpret_cast<half4*>(dst) = y;
+        } else if (keep_lo) {
+            *reinterpret_cast<half2v*>(dst) = half2v{y[0], y[1]};
+        } else {
+            *reinterpret_cast<half2v*>(dst + 2) = half2v{y[2], y[3]};
         }
     }
 }
@@ -156,10 +182,12 @@ static hipError_t launch_decode_t(const LinearPlan& p, const uint16_t* X, int64_
                                   hipStream_t stream)
 {
     uint32_t* counters = reinterpret_cast<uint32_t*>(workspace);
-    float4v* partials = reinterpret_cast<float4v*>(reinterpret_cast<char*>(workspace) + kCounterBytes);
+    float4v* partials = reinterpret_cast<float4v*>(reinterpret_cast<char*>(workspace) + kZeroBytes);
+    unsigned long long* slots = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(workspace) + kCounterBytes);
     const unsigned grid = (unsigned)((N / kTile) * p.split_k);
     hipLaunchKernelGGL((decode_kernel<WAVES, D>), dim3(grid), dim3(WAVES * 64), 0, stream, X, (int)M,
-                       (const u32x4*)hi, (const u32x4*)lo, scales, (int)N, (int)K, Y, partials, counters, p.split_k);
+                       (const u32x4*)hi, (const u32x4*)lo, scales, (int)N, (int)K, Y, partials, counters, slots,
+                       p.split_k, p.pairwise);
     return hipGetLastError();
 }
 

@@ -234,7 +234,7 @@ __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
 #pragma unroll
                 for (int t = 0; t < NT; t++) store_partial(win, (a * NT + t) * THREADS + tid2, acc[a][t]);
         }
-        if (!arrive_last(&counters[tile], (uint32_t)split_k)) return;
+        if (!arrive_last(&counters[tile * kCounterStride], (uint32_t)split_k)) return;
 #pragma unroll
         for (int a = 0; a < MT; a++)
 #pragma unroll
@@ -294,7 +294,7 @@ static hipError_t launch_gemm_t(const LinearPlan& p, const uint16_t* X, int64_t 
                                 hipStream_t stream)
 {
     uint32_t* counters = reinterpret_cast<uint32_t*>(workspace);
-    float4v* partials = reinterpret_cast<float4v*>(reinterpret_cast<char*>(workspace) + kCounterBytes);
+    float4v* partials = reinterpret_cast<float4v*>(reinterpret_cast<char*>(workspace) + kZeroBytes);
     const int64_t mblk = (M + BM - 1) / BM, nblk = (N / kTile + kGemmBlocksN - 1) / kGemmBlocksN;
     const unsigned grid = (unsigned)(nblk >= 8 ? mblk * ((nblk + 7) / 8 * 8) * p.split_k
                                                : mblk * ((nblk * p.split_k + 7) / 8 * 8));   // padded: see the id mapping

@@ -7,9 +7,14 @@
 
 namespace fp6 {
 
-// Workspace layout: [counters: kCounterBytes][fp32 partial sums]
-constexpr size_t kCounterBytes = 16384;
-constexpr int kMaxCounters = (int)(kCounterBytes / sizeof(uint32_t));
+// Workspace layout: [arrival counters: kCounterBytes][meeting slots: kSlotBytes][fp32 partial sums].
+// The first two regions (kZeroBytes) are zero whenever no call is running.
+constexpr int kCounterStride = 16;      // uint32 words between two counters: one 64-byte line each, so that
+                                        // arrivals at different tiles do not queue up behind one another
+constexpr int kMaxCounters = 1024;
+constexpr size_t kCounterBytes = (size_t)kMaxCounters * kCounterStride * sizeof(uint32_t);
+constexpr size_t kSlotBytes = (size_t)4 << 20;
+constexpr size_t kZeroBytes = kCounterBytes + kSlotBytes;
 
 hipError_t launch_quantize_pack(const uint16_t* W, int64_t N, int64_t K, void* hi, void* lo, uint16_t* scales,
                                 hipStream_t stream);
@@ -27,6 +32,7 @@ struct LinearPlan {
     int depth;          // tiles in the per-wavefront prefetch ring
     size_t partial_bytes;   // fp32 partial sums needed in the workspace (0 if split_k == 1)
     int counters;       // arrival counters used (0 if split_k == 1)
+    int pairwise;       // DECODE with split_k > 1: K-slices meet pairwise in the slot region (1) or at a counter (0)
 };
 
 // Heuristic (or caller-forced) plan; returns false if the request is invalid for the shape.

@@ -51,4 +51,55 @@ __device__ __forceinline__ bool arrive_last(uint32_t* counter, uint32_t expected
     return s_last != 0u;
 }
 
+// ---- Pairwise meeting: a second way for K-slices to be added, for small partial sums.
+//
+// Two parties meet in a 64-bit slot that is zero when idle.  Each swaps its two fp32
+// values (encoded so that they are never zero) into the slot with one agent-scope atomic
+// exchange.  Whoever gets zero back came first and is done: its values now wait in the
+// slot.  Whoever gets values back came second: it adds them to its own, writes zero back
+// and carries the sum on.  One memory round trip, no barrier and no waiting; which party
+// carries on depends on timing, the sum does not (a + b == b + a in IEEE arithmetic).
+// More than two slices meet in a binary tree over the slice index, so the association
+// order ((s0+s1)+(s2+s3))+... is fixed as well.
+struct Pair {
+    float a, b;
+};
+
+__device__ __forceinline__ uint32_t nonzero_code(float v)
+{
+    uint32_t w = ~__builtin_bit_cast(uint32_t, v);
+    return w ? w : ~0x7FC00000u;      // the all-ones NaN pattern is posted as the default NaN
+}
+__device__ __forceinline__ float from_code(uint32_t w) { return __builtin_bit_cast(float, ~w); }
+
+// Returns true if this caller carries the sum (then `v` holds it), false if it is done.
+__device__ __forceinline__ bool meet_pair(unsigned long long* slot, Pair& v)
+{
+    const unsigned long long mine = ((unsigned long long)nonzero_code(v.b) << 32) | nonzero_code(v.a);
+    const unsigned long long other = __hip_atomic_exchange(slot, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (other == 0ull) return false;
+    __hip_atomic_store(slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    v.a += from_code((uint32_t)other);
+    v.b += from_code((uint32_t)(other >> 32));
+    return true;
+}
+
+// Tree over `count` slices; `index` is this caller's slice.  `slots` points at this
+// value pair's first slot; consecutive tree nodes are `node_stride` slots apart and
+// count - 1 of them are used.  Returns true for exactly one of the `count` callers,
+// with the total in `v`.
+__device__ __forceinline__ bool meet_tree(unsigned long long* slots, size_t node_stride, int index, int count, Pair& v)
+{
+    int node0 = 0;
+    while (count > 1) {
+        if ((index ^ 1) < count) {
+            if (!meet_pair(slots + (size_t)(node0 + (index >> 1)) * node_stride, v)) return false;
+        }
+        node0 += count >> 1;
+        index >>= 1;
+        count = (count + 1) >> 1;
+    }
+    return true;
+}
+
 }  // namespace fp6

@@ -70,17 +70,25 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert L.fp6_linear_variant(a, 1, a, a, a, 64, 256, a, None, 0, None, 7, 0) == -5
     # workspace: a split needs one
     need = B.fp6_linear_variant_workspace_bytes(1, 64, 256, B.FP6_VARIANT_DECODE, 2)
-    assert need > B.FP6_WORKSPACE_COUNTER_BYTES
+    assert need >= B.FP6_WORKSPACE_ZERO_BYTES
     assert L.fp6_linear_variant(a, 1, a, a, a, 64, 256, a, None, 0, None, B.FP6_VARIANT_DECODE, 2) == -4
     assert L.fp6_linear_variant(a, 1, a, a, a, 64, 256, a, a, need - 1, None, B.FP6_VARIANT_DECODE, 2) == -4
 
 
 def test_workspace_bytes():
     assert B.fp6_linear_variant_workspace_bytes(1, 64, 64, B.FP6_VARIANT_DECODE, 1) == 0
-    assert B.fp6_linear_variant_workspace_bytes(1, 1024, 1024, B.FP6_VARIANT_DECODE, 4) == \
-        B.FP6_WORKSPACE_COUNTER_BYTES + 4 * 16 * 64 * 16 * 4
+    # small M: the slices meet pairwise inside the zero region; at a counter they need a buffer
+    assert B.fp6_linear_variant_workspace_bytes(1, 1024, 1024, B.FP6_VARIANT_DECODE, 2) == B.FP6_WORKSPACE_ZERO_BYTES
+    assert B.fp6_linear_variant_workspace_bytes(1, 1024, 1024, B.FP6_VARIANT_DECODE | B.FP6_HINT_MEET(2), 4) == \
+        B.FP6_WORKSPACE_ZERO_BYTES
+    assert B.fp6_linear_variant_workspace_bytes(1, 1024, 1024, B.FP6_VARIANT_DECODE | B.FP6_HINT_MEET(1), 4) == \
+        B.FP6_WORKSPACE_ZERO_BYTES + 4 * 16 * 64 * 16 * 4
+    assert B.fp6_linear_variant_workspace_bytes(16, 1024, 1024, B.FP6_VARIANT_DECODE, 4) == \
+        B.FP6_WORKSPACE_ZERO_BYTES + 4 * 16 * 64 * 16 * 4
+    # pairwise meeting that does not fit the slot region is refused
+    assert B.fp6_linear_variant_workspace_bytes(16, 32768, 8192, B.FP6_VARIANT_DECODE | B.FP6_HINT_MEET(2), 4) == 0
     assert B.fp6_linear_variant_workspace_bytes(100, 512, 1024, B.FP6_VARIANT_GEMM, 2) == \
-        B.FP6_WORKSPACE_COUNTER_BYTES + 2 * 2 * 128 * 256 * 4
+        B.FP6_WORKSPACE_ZERO_BYTES + 2 * 2 * 128 * 256 * 4
     assert B.fp6_linear_workspace_bytes(0, 64, 64) == 0          # invalid shapes need nothing
     for M, N, K in [(1, 4096, 4096), (16, 8192, 28672), (512, 8192, 28672), (128, 5120, 13824)]:
         assert B.fp6_linear_workspace_bytes(M, N, K) % 16 == 0

@@ -199,6 +199,30 @@ def test_constant_code_closed_form():
             assert torch.all(Y.double() == 2.0 ** -6 * O.e3m2_value(c) * K), (c, variant)
 
 
+@pytest.mark.parametrize("M", [1, 2, 4, 5, 16])
+@pytest.mark.parametrize("split", [2, 3, 4, 6, 8, 12, 24])
+@pytest.mark.parametrize("meet", [1, 2])
+def test_decode_slices_meet_at_counter_or_pairwise(M, split, meet):
+    # both ways of adding K-slices, split counts that are not powers of two (tree nodes with a
+    # single child), one workspace shared by every call and left zero by each
+    N, K = 192, 64 * 24
+    B = P.binding
+    W = inputs.weight(N, K, seed=700 + split, sigma=0.02, outlier_frac=0.001, device=DEV)
+    X = inputs.activation(M, K, seed=710 + M, device=DEV)
+    hi, lo, sc = _quant(W)
+    _, _, Yref = oracle_reference(W, X)
+    variant = P.FP6_VARIANT_DECODE | B.FP6_HINT_MEET(meet)
+    ws = P.new_workspace(P.fp6_linear_variant_workspace_bytes(M, N, K, P.FP6_VARIANT_DECODE | B.FP6_HINT_MEET(1), split), DEV)
+    Ya = P.fp6_linear_variant(X, hi, lo, sc, N, K, variant, split, workspace=ws)
+    assert_y_close(Ya, Yref, (M, split, meet))
+    # the other protocol on the same workspace, then this one again: bit-identical, zero region clean
+    P.fp6_linear_variant(X, hi, lo, sc, N, K, P.FP6_VARIANT_DECODE | B.FP6_HINT_MEET(3 - meet), split, workspace=ws)
+    Yb = P.fp6_linear_variant(X, hi, lo, sc, N, K, variant, split, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(Ya, Yb)
+    assert torch.count_nonzero(ws[:B.FP6_WORKSPACE_ZERO_BYTES]).item() == 0
+
+
 def test_split_and_unsplit_agree_and_workspace_is_reusable():
     N, K, M = 512, 2048, 8
     W = inputs.weight(N, K, seed=31, sigma=0.02, outlier_frac=0.001, device=DEV)
@@ -216,7 +240,7 @@ def test_split_and_unsplit_agree_and_workspace_is_reusable():
         d = (Y1.float() - Y8.float()).abs().max().item()
         assert d <= 2e-3 * Y1.float().abs().max().item()
         ys.append(Y8)
-    assert torch.count_nonzero(ws[:P.binding.FP6_WORKSPACE_COUNTER_BYTES]).item() == 0
+    assert torch.count_nonzero(ws[:P.binding.FP6_WORKSPACE_ZERO_BYTES]).item() == 0
     assert not torch.equal(ys[0], ys[1])
 
 
