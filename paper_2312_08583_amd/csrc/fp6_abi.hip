@@ -14,15 +14,20 @@ static bool shape_ok(int64_t N, int64_t K)
            K <= (int64_t)1 << 30 && N * K <= (int64_t)1 << 40;
 }
 
-// largest divisor d of `ktiles` with units*d <= capacity (workgroups that can be resident
-// at once: a second round of workgroups costs more than it gains) and ktiles/d >= min_tiles
-static int pick_split(int64_t units, int64_t ktiles, int64_t capacity, int64_t min_tiles)
+// Number of K-slices for the decode family (measured on MI355X at M = 1).  The stream wants at
+// least one workgroup per compute unit; beyond ~1.5 per unit more slices only add to the tail,
+// where the slices' partial sums meet.  Two slices meet pairwise, which is cheaper than any
+// larger number, so two is taken whenever it fills the chip.  Every wavefront keeps >= 2 tiles.
+static int pick_decode_split(int64_t units, int64_t ktiles, int waves)
 {
+    if (units >= 384) return 1;
+    if (units * 2 >= 256 && ktiles % 2 == 0 && ktiles / 2 >= 2 * waves) return 2;
     int best = 1;
     for (int64_t d = 1; d <= ktiles; d++) {
         if (ktiles % d) continue;
-        if (ktiles / d < min_tiles || units * d > capacity) break;
+        if (ktiles / d < 2 * waves) break;
         best = (int)d;
+        if (units * d >= 256) break;
     }
     return best;
 }
@@ -51,8 +56,7 @@ bool make_plan(int64_t M, int64_t N, int64_t K, int variant, int split_k, Linear
         p.depth = hint_depth ? hint_depth : 4;
         tiles = nblocks;
         regs_per_tile = 256;                       // float4 per output tile (64 x 16 fp32)
-        // up to 3 workgroups per compute unit are resident; at least two tiles per wavefront
-        p.split_k = split_k ? split_k : pick_split(nblocks, ktiles, 768, 2 * p.waves);
+        p.split_k = split_k ? split_k : pick_decode_split(nblocks, ktiles, p.waves);
     } else {
         if ((hint_waves && hint_waves != 4 && hint_waves != 8) || hint_depth || hint_meet ||
             (hint_bm && hint_bm != 32 && hint_bm != 64 && hint_bm != 128))
