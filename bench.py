@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fp16-baseline", action="store_true")
     ap.add_argument("--legs", default="1,512", help="comma-separated M values to time")
+    ap.add_argument("--no-ablation", action="store_true",
+                    help="skip the bias-shift ablation on the paper's kernel-table shapes")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates the HBM byte counters of a profiler run)")
     return ap.parse_args()
@@ -151,6 +153,37 @@ def main():
             fp16[str(M)] = dict(ms_per_step=e0.elapsed_time(e1) / n)
         del dense
 
+    # ---- bias-shift ablation (Section 5.3: the same kernel without bias shift) on the six
+    # feed-forward shapes of the paper's kernel table (Appendix B), batch 8, cold weights
+    ablation = None
+    if not args.no_ablation:
+        B = P.binding
+        modes = {"bias_shift": 0, "integer_rebias": B.FP6_HINT_DEQUANT(1), "fp16_multiply": B.FP6_HINT_DEQUANT(2)}
+        tcfg = inputs.WORKLOADS["paper_table_b1"]
+        M = tcfg["Ms"][0]
+        ablation = {"M": M, "unit": "us", "shapes": {}}
+        for si, (name, N, K) in enumerate(tcfg["shapes"]):
+            W = inputs.workload_weight("paper_table_b1", si, device=dev)
+            hi, lo, sc = P.fp6_quantize_pack(W)
+            del W
+            copies = max(2, min(64, int(1.0e9 / (0.75 * N * K))))
+            pool = [(hi.clone(), lo.clone()) for _ in range(copies)]
+            X = inputs.activation(M, K, seed=inputs.workload_seed("paper_table_b1", 500 + si), device=dev)
+            Y = torch.empty((M, N), dtype=torch.float16, device=dev)
+            row = {}
+            for mode, hint in modes.items():
+                ws = P.new_workspace(max(P.fp6_linear_variant_workspace_bytes(M, N, K, hint, 0), 16), dev)
+
+                def sweep():
+                    for (h, l) in pool:
+                        P.fp6_linear_variant(X, h, l, sc, N, K, hint, 0, out=Y, workspace=ws)
+                row[mode] = round(time_passes(sweep, 5, 2) * 1e3 / copies, 2)
+            ablation["shapes"]["%s %dx%d" % (name, N, K)] = row
+            del pool
+        for mode in ("integer_rebias", "fp16_multiply"):
+            r = [v[mode] / v["bias_shift"] for v in ablation["shapes"].values()]
+            ablation["mean_slowdown_" + mode] = round(sum(r) / len(r), 3)
+
     # ---- CPU oracle on a bounded sample of the same workload (reported baseline)
     cpu = None
     if not args.no_cpu_baseline:
@@ -211,6 +244,8 @@ def main():
                        "roofline": {"bound": "mfma", "achieved": r["tflops"], "peak": MFMA_FP16_PEAK_TFLOPS,
                                     "unit": "TFLOP/s", "frac": r["tflops"] / MFMA_FP16_PEAK_TFLOPS, "traffic": traffic.get(512),
                                     "kernel": "gemm_kernel (block_m 128), all %d launches of a step" % launches}}
+    if ablation is not None:
+        out["bias_shift_ablation"] = ablation
     if fp16 is not None:
         out["fp16_dense_baseline"] = {"kind": "torch.matmul (hipBLASLt) on the dequantized fp16 weights, same stack",
                                       "ms_per_step": {m: v["ms_per_step"] for m, v in fp16.items()}}

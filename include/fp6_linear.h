@@ -159,12 +159,20 @@ int fp6_linear(const uint16_t *X, int64_t M, const void *hi_plane, const void *l
  *   FP6_HINT_BLOCK_M(b) rows of X per workgroup, gemm family: 32, 64 or 128
  *   FP6_HINT_MEET(x)    decode family with split_k > 1: 1 = K-slices meet at an arrival counter,
  *                       2 = pairwise in slots (needs split_k * (N/64) * 256 * M <= 2^22)
+ *   FP6_HINT_DEQUANT(x) ablations of the bias shift (Section 5.2): the sub-numbers are turned into the
+ *                       fp16 numbers that equal the FP6 values themselves and the row scale is applied
+ *                       without the 2^12.  1 = integer arithmetic on the exponent field (+12, FP6
+ *                       subnormals special-cased: the traditional dequantization the paper compares
+ *                       against); 2 = one fp16 multiply by 2^12 per pair of weights.  Same results as
+ *                       the bias shift; they exist to measure what it saves.  Not combinable with
+ *                       FP6_HINT_WAVES / FP6_HINT_DEPTH.
  * An unsupported combination returns FP6_ERR_VARIANT.
  */
 #define FP6_HINT_WAVES(w) ((int)(w) << 8)
 #define FP6_HINT_DEPTH(d) ((int)(d) << 12)
 #define FP6_HINT_BLOCK_M(b) (((int)(b) / 16) << 16)
 #define FP6_HINT_MEET(x) ((int)(x) << 20)
+#define FP6_HINT_DEQUANT(x) ((int)(x) << 22)
 size_t fp6_linear_variant_workspace_bytes(int64_t M, int64_t N, int64_t K, int variant, int split_k);
 int fp6_linear_variant(const uint16_t *X, int64_t M, const void *hi_plane, const void *lo_plane,
                        const uint16_t *scales, int64_t N, int64_t K, uint16_t *Y,

@@ -37,6 +37,10 @@ def FP6_HINT_MEET(x: int) -> int:
     return int(x) << 20
 
 
+def FP6_HINT_DEQUANT(x: int) -> int:
+    return int(x) << 22
+
+
 EXPORTS = ["fp6_layout_version", "fp6_status_string", "fp6_packed_sizes", "fp6_quantize_pack",
            "fp6_unpack_codes", "fp6_dequantize", "fp6_linear_workspace_bytes", "fp6_linear",
            "fp6_linear_variant_workspace_bytes", "fp6_linear_variant"]

@@ -37,7 +37,7 @@ bool make_plan(int64_t M, int64_t N, int64_t K, int variant, int split_k, Linear
     const int64_t ktiles = K / FP6_TILE, nblocks = N / FP6_TILE;
     // tuning hints ride in the upper bits of `variant`; 0 = automatic
     const int hint_waves = (variant >> 8) & 0xF, hint_depth = (variant >> 12) & 0xF, hint_bm = ((variant >> 16) & 0xF) * 16,
-              hint_meet = (variant >> 20) & 0x3;
+              hint_meet = (variant >> 20) & 0x3, hint_dequant = (variant >> 22) & 0x3;
     variant &= 0xFF;
     if (variant == FP6_VARIANT_AUTO) variant = (M <= 16) ? FP6_VARIANT_DECODE : FP6_VARIANT_GEMM;
     if (variant != FP6_VARIANT_DECODE && variant != FP6_VARIANT_GEMM) return false;
@@ -46,6 +46,9 @@ bool make_plan(int64_t M, int64_t N, int64_t K, int variant, int split_k, Linear
 
     LinearPlan p{};
     p.variant = variant;
+    p.dequant = hint_dequant;
+    // the ablations exist for the default kernel configurations only
+    if (hint_dequant > 2 || (hint_dequant && (hint_waves || hint_depth))) return false;
     int64_t tiles, regs_per_tile;
     if (variant == FP6_VARIANT_DECODE) {
         if ((hint_waves && hint_waves != 4 && hint_waves != 8) || (hint_depth && (hint_depth < 2 || hint_depth > 4)) || hint_bm ||

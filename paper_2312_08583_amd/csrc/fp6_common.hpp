@@ -63,23 +63,65 @@ __device__ __forceinline__ uint32_t tile_lo_dword(const TileRaw& r, int f) { ret
 //   byte b of L: bits1..0 mant(grp0) bits3..2 mant(grp1)
 // Byte b carries element j = 2*(b&1) + (b>>1) of its group: bytes 0 and 2 become the low
 // and high half of one operand register (elements 0,1), bytes 1 and 3 those of the next.
+//
+// How the padded sub-numbers become the fp16 MFMA operand:
+//   kBiasShift   the method (Section 5.2, Eq. 5): nothing more is done; the operand is the FP6
+//                value times 2^-12 and the 2^12 rides in the scale.
+//   kIntRebias   ablation, the traditional dequantization of Section 5.2: integer arithmetic on
+//                the exponent field (+12 = fp16 bias 15 - FP6 bias 3), FP6 subnormals special-cased.
+//   kHalfMul     ablation: the padded pattern is multiplied by 2^12 in fp16, i.e. the
+//                floating-point unit does the exponent arithmetic (subnormals included).
+// The ablations produce the FP6 values themselves, and the row scale is applied without 2^12.
+enum Dequant { kBiasShift = 0, kIntRebias = 1, kHalfMul = 2 };
+
+// Four bytes  s g g e e e m m  ->  the top bytes of the fp16 numbers equal to the FP6 values:
+// exponent field + 12 for normal numbers; the FP6 subnormals m/16 are normal numbers in fp16
+// and are rebuilt case by case (0 -> 0, 1 -> 2^-4, 2 -> 2^-3, 3 -> 1.5 * 2^-3).
+__device__ __forceinline__ uint32_t rebias_bytes(uint32_t u)
+{
+    u &= 0x9F9F9F9Fu;                                               // drop the don't-care bits
+    const uint32_t e = u & 0x1C1C1C1Cu;
+    const uint32_t nz = ((e | (e >> 1) | (e >> 2)) >> 2) & 0x01010101u;   // 1 in a byte: exponent field != 0
+    const uint32_t normal = (nz << 8) - nz;                         // 0xFF in the bytes of normal numbers
+    const uint32_t n = u + 0x30303030u;                             // 12 << 2 per byte; eee + 12 <= 19: no carry out
+    const uint32_t m0 = u & 0x01010101u, m1 = (u >> 1) & 0x01010101u;
+    const uint32_t any = m0 | m1, one = m0 & ~m1, three = m0 & m1;
+    // subnormal bytes: sign | exponent 11 (m = 1) or 12 (m = 2, 3) | top mantissa bit (m = 3)
+    const uint32_t sub = (u & 0x80808080u) | (any << 5) | (m1 << 4) | (one << 3) | (one << 2) | (three << 1);
+    return bit_select(n, sub, normal);
+}
+
+template <int DQ = kBiasShift>
 __device__ __forceinline__ half8 unpack_fragment(uint32_t H, uint32_t L)
 {
     // s g g e e e m m per byte (g = don't-care bits removed by the final masks)
     uint32_t u0 = bit_select(H << 7, bit_select(H, L, 0x1C1C1C1Cu), 0x80808080u);
     uint32_t u1 = bit_select(H << 6, bit_select(H >> 3, L >> 2, 0x1C1C1C1Cu), 0x80808080u);
+    if (DQ == kIntRebias) {
+        u0 = rebias_bytes(u0);
+        u1 = rebias_bytes(u1);
+    }
+    constexpr uint32_t kKeep = DQ == kIntRebias ? 0xFF00FF00u : 0x9F009F00u;
     u32x4 w;
-    w.x = (u0 << 8) & 0x9F009F00u;   // bytes 0,2 -> elements 0,1
-    w.y = u0 & 0x9F009F00u;          // bytes 1,3 -> elements 2,3
-    w.z = (u1 << 8) & 0x9F009F00u;   // elements 4,5
-    w.w = u1 & 0x9F009F00u;          // elements 6,7
-    return __builtin_bit_cast(half8, w);
+    w.x = (u0 << 8) & kKeep;   // bytes 0,2 -> elements 0,1
+    w.y = u0 & kKeep;          // bytes 1,3 -> elements 2,3
+    w.z = (u1 << 8) & kKeep;   // elements 4,5
+    w.w = u1 & kKeep;          // elements 6,7
+    half8 h = __builtin_bit_cast(half8, w);
+    if (DQ == kHalfMul) h *= (_Float16)4096.0f;
+    return h;
 }
 
+template <int DQ = kBiasShift>
 __device__ __forceinline__ half8 unpack_tile_fragment(const TileRaw& r, int f)
 {
-    return unpack_fragment(tile_hi_dword(r, f), tile_lo_dword(r, f) >> (4 * (f & 1)));
+    return unpack_fragment<DQ>(tile_hi_dword(r, f), tile_lo_dword(r, f) >> (4 * (f & 1)));
 }
+
+// What the accumulated sum has to be multiplied by besides the row scale: the 2^12 that the
+// bias shift took out of every weight (Section 5.2, Eq. 5), or nothing.
+template <int DQ>
+constexpr float kUnshift = DQ == kBiasShift ? 4096.0f : 1.0f;
 
 // D(16x16, fp32) += A(16x32 fp16) * B(32x16 fp16).  Lane l supplies row l%16 of A and
 // column l%16 of B for the eight k values of group l/16, and holds D[4*(l/16)+r][l%16].

@@ -33,18 +33,19 @@ __device__ __forceinline__ XFrag load_x(const uint16_t* __restrict__ xrow, int k
     return x;
 }
 
+template <int DQ>
 __device__ __forceinline__ void tile_mac(const TileRaw& r, const XFrag& x, float4v acc[4])
 {
 #pragma unroll
     for (int f = 0; f < 8; f++) {
-        half8 w = unpack_tile_fragment(r, f);
+        half8 w = unpack_tile_fragment<DQ>(r, f);
         acc[f >> 1] = mfma16x16x32(w, (f & 1) ? x.q1 : x.q0, acc[f >> 1]);
     }
 }
 
 // D = depth of the per-wavefront ring of tiles in flight (D-1 tiles are being fetched
 // while one is consumed).  The ring is indexed with compile-time constants only.
-template <int WAVES, int D>
+template <int WAVES, int D, int DQ>
 __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
     const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
@@ -91,7 +92,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
                 const int k = kt0 + (j0 + u + D - 1) * WAVES;
                 raw[(u + D - 1) % D] = load_tile(hi, lo, tile0 + k, lane);
                 xf[(u + D - 1) % D] = load_x(xrow, k);
-                tile_mac(raw[u], xf[u], acc);
+                tile_mac<DQ>(raw[u], xf[u], acc);
             }
         }
         // drain: the remaining (< 2D-1) tiles, refilling only while tiles are left
@@ -104,7 +105,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
                     raw[(v + D - 1) % D] = load_tile(hi, lo, tile0 + k, lane);
                     xf[(v + D - 1) % D] = load_x(xrow, k);
                 }
-                tile_mac(raw[v % D], xf[v % D], acc);
+                tile_mac<DQ>(raw[v % D], xf[v % D], acc);
             }
         }
     }
@@ -164,7 +165,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     if (keep_lo || keep_hi) {
         half4 y;
 #pragma unroll
-        for (int r = 0; r < 4; r++) y[r] = (_Float16)(sum[r] * ((float)sc[r] * 4096.0f));
+        for (int r = 0; r < 4; r++) y[r] = (_Float16)(sum[r] * ((float)sc[r] * kUnshift<DQ>));
         uint16_t* dst = Y + (size_t)mm * N + nb * kTile + n4 * 4;
         if (keep_lo && keep_hi) {
             *reinterpret_cast<half4*>(dst) = y;
@@ -176,7 +177,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     }
 }
 
-template <int WAVES, int D>
+template <int WAVES, int D, int DQ = kBiasShift>
 static hipError_t launch_decode_t(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
                                   const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                                   hipStream_t stream)
@@ -185,7 +186,7 @@ static hipError_t launch_decode_t(const LinearPlan& p, const uint16_t* X, int64_
     float4v* partials = reinterpret_cast<float4v*>(reinterpret_cast<char*>(workspace) + kZeroBytes);
     unsigned long long* slots = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(workspace) + kCounterBytes);
     const unsigned grid = (unsigned)((N / kTile) * p.split_k);
-    hipLaunchKernelGGL((decode_kernel<WAVES, D>), dim3(grid), dim3(WAVES * 64), 0, stream, X, (int)M,
+    hipLaunchKernelGGL((decode_kernel<WAVES, D, DQ>), dim3(grid), dim3(WAVES * 64), 0, stream, X, (int)M,
                        (const u32x4*)hi, (const u32x4*)lo, scales, (int)N, (int)K, Y, partials, counters, slots,
                        p.split_k, p.pairwise);
     return hipGetLastError();
@@ -195,6 +196,8 @@ hipError_t launch_decode(const LinearPlan& p, const uint16_t* X, int64_t M, cons
                          const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                          hipStream_t stream)
 {
+    if (p.dequant == kIntRebias) return launch_decode_t<4, 4, kIntRebias>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+    if (p.dequant == kHalfMul) return launch_decode_t<4, 4, kHalfMul>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     switch (p.waves * 10 + p.depth) {
         case 42: return launch_decode_t<4, 2>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
         case 43: return launch_decode_t<4, 3>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);

@@ -59,7 +59,7 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
-template <int BM, int D, int WN>
+template <int BM, int D, int WN, int DQ>
 __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
     const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
     const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
             }
 #pragma unroll
             for (int t = 0; t < NT; t++) {
-                half8 w = unpack_tile_fragment(raw[t / 4], 2 * (t % 4) + q);
+                half8 w = unpack_tile_fragment<DQ>(raw[t / 4], 2 * (t % 4) + q);
 #pragma unroll
                 for (int a = 0; a < MT; a++) acc[a][t] = mfma16x16x32(w, xf[a], acc[a][t]);
             }
@@ -270,7 +270,7 @@ __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
         for (int t = 0; t < 4; t++) {
             const half4 h = *reinterpret_cast<const half4*>(scales + (size_t)nb * kTile + t * 16 + g2 * 4);
 #pragma unroll
-            for (int r = 0; r < 4; r++) sc[t][r] = (float)h[r] * 4096.0f;
+            for (int r = 0; r < 4; r++) sc[t][r] = (float)h[r] * kUnshift<DQ>;
         }
 #pragma unroll
         for (int a = 0; a < MT; a++) {
@@ -288,7 +288,7 @@ __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
     }
 }
 
-template <int BM, int D, int WN>
+template <int BM, int D, int WN, int DQ = kBiasShift>
 static hipError_t launch_gemm_t(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
                                 const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                                 hipStream_t stream)
@@ -298,7 +298,7 @@ static hipError_t launch_gemm_t(const LinearPlan& p, const uint16_t* X, int64_t 
     const int64_t mblk = (M + BM - 1) / BM, nblk = (N / kTile + kGemmBlocksN - 1) / kGemmBlocksN;
     const unsigned grid = (unsigned)(nblk >= 8 ? mblk * ((nblk + 7) / 8 * 8) * p.split_k
                                                : mblk * ((nblk * p.split_k + 7) / 8 * 8));   // padded: see the id mapping
-    hipLaunchKernelGGL((gemm_kernel<BM, D, WN>), dim3(grid), dim3(kGemmBlocksN / WN * 64), 0, stream, X, (int)M,
+    hipLaunchKernelGGL((gemm_kernel<BM, D, WN, DQ>), dim3(grid), dim3(kGemmBlocksN / WN * 64), 0, stream, X, (int)M,
                        (const u32x4*)hi, (const u32x4*)lo, scales, (int)N, (int)K, Y, partials, counters, p.split_k);
     return hipGetLastError();
 }
@@ -307,7 +307,13 @@ hipError_t launch_gemm(const LinearPlan& p, const uint16_t* X, int64_t M, const 
                        const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                        hipStream_t stream)
 {
-    switch (p.block_m * 10 + p.waves) {
+    switch (p.block_m * 10 + p.waves + p.dequant * 10000) {
+        case 10328: return launch_gemm_t<32, 4, 1, kIntRebias>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        case 10648: return launch_gemm_t<64, 4, 1, kIntRebias>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        case 11288: return launch_gemm_t<128, 3, 1, kIntRebias>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        case 20328: return launch_gemm_t<32, 4, 1, kHalfMul>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        case 20648: return launch_gemm_t<64, 4, 1, kHalfMul>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        case 21288: return launch_gemm_t<128, 3, 1, kHalfMul>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
         case 328: return launch_gemm_t<32, 4, 1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
         case 324: return launch_gemm_t<32, 4, 2>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
         case 648: return launch_gemm_t<64, 4, 1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);

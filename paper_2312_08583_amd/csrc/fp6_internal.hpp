@@ -32,6 +32,7 @@ struct LinearPlan {
     int depth;          // tiles in the per-wavefront prefetch ring
     size_t partial_bytes;   // fp32 partial sums needed in the workspace (0 if split_k == 1)
     int counters;       // arrival counters used (0 if split_k == 1)
+    int dequant;        // 0: bias-shift unpack (the method); 1, 2: ablations (integer re-bias, fp16 multiply)
     int pairwise;       // DECODE with split_k > 1: K-slices meet pairwise in the slot region (1) or at a counter (0)
 };
 

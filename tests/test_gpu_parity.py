@@ -121,7 +121,11 @@ def test_quantize_of_dequantized_is_identity_on_gpu():
 
 # ------------------------------------------------------------------ hot path
 
-VARIANTS = [(P.FP6_VARIANT_DECODE, 1), (P.FP6_VARIANT_DECODE, 2), (P.FP6_VARIANT_GEMM, 1), (P.FP6_VARIANT_GEMM, 2)]
+NO_BS = P.binding.FP6_HINT_DEQUANT(1)     # ablation: integer exponent arithmetic instead of the bias shift
+HMUL = P.binding.FP6_HINT_DEQUANT(2)      # ablation: fp16 multiply by 2^12
+VARIANTS = [(P.FP6_VARIANT_DECODE, 1), (P.FP6_VARIANT_DECODE, 2), (P.FP6_VARIANT_GEMM, 1), (P.FP6_VARIANT_GEMM, 2),
+            (P.FP6_VARIANT_DECODE | NO_BS, 1), (P.FP6_VARIANT_DECODE | NO_BS, 4), (P.FP6_VARIANT_GEMM | NO_BS, 1),
+            (P.FP6_VARIANT_GEMM | NO_BS, 2), (P.FP6_VARIANT_DECODE | HMUL, 2), (P.FP6_VARIANT_GEMM | HMUL, 1)]
 
 
 @pytest.mark.parametrize("variant,split", VARIANTS)
@@ -144,7 +148,7 @@ def test_one_hot_rows_read_back_dequantized_weights_bit_exact(variant, split):
         X = torch.zeros((len(cols), K), dtype=torch.float16, device=DEV)
         for m, k in enumerate(cols):
             X[m, k] = 1.0
-        if variant == P.FP6_VARIANT_GEMM:
+        if variant & 0xFF == P.FP6_VARIANT_GEMM:
             X = torch.cat([X, X, X[:1]])                           # M = 33: ragged
         Y = P.fp6_linear_variant(X, hi_d, lo_d, sc_d, N, K, variant, split)
         torch.cuda.synchronize()
@@ -221,6 +225,24 @@ def test_decode_slices_meet_at_counter_or_pairwise(M, split, meet):
     torch.cuda.synchronize()
     assert torch.equal(Ya, Yb)
     assert torch.count_nonzero(ws[:B.FP6_WORKSPACE_ZERO_BYTES]).item() == 0
+
+
+@pytest.mark.parametrize("M", [1, 16, 40, 100, 300])
+@pytest.mark.parametrize("ablation", [NO_BS, HMUL])
+def test_no_bias_shift_ablation_matches_oracle_and_the_bias_shift_path(M, ablation):
+    # Section 5.2 ablation: same numbers by run-time exponent arithmetic.  Every product and the
+    # scale multiply are the same real numbers times an exact power of two, so with the same
+    # summation order the two paths agree bit for bit.
+    N, K = 640, 1024
+    W = inputs.weight(N, K, seed=900 + M, sigma=0.02, outlier_frac=0.001, device=DEV)
+    X = inputs.activation(M, K, seed=910 + M, device=DEV)
+    hi, lo, sc = _quant(W)
+    _, _, Yref = oracle_reference(W, X)
+    fam = P.FP6_VARIANT_DECODE if M <= 16 else P.FP6_VARIANT_GEMM
+    Ya = P.fp6_linear_variant(X, hi, lo, sc, N, K, fam | ablation, 1)
+    Yb = P.fp6_linear_variant(X, hi, lo, sc, N, K, fam, 1)
+    assert_y_close(Ya, Yref, (M, "ablation"))
+    assert torch.equal(Ya, Yb)
 
 
 def test_split_and_unsplit_agree_and_workspace_is_reusable():
