@@ -26,7 +26,8 @@
  *                      are an fp16 bit pattern (pure padding) whose value is the FP6
  *                      value times 2^-12; the 2^12 moves into the scale.
  *   linear ........... Section 5.2: for row-wise scales the scale multiplies the
- *                      finished accumulation.
+ *                      finished accumulation; for fine-grained (block-k) scales it
+ *                      multiplies each block's product sum before the accumulation.
  *
  * Readings taken where the paper is silent (listed again in the design notes):
  *   - round-to-nearest ties go to the even magnitude code (IEEE default);
@@ -250,6 +251,88 @@ void fp6o_linear(const uint16_t *X, int64_t M, const uint8_t *codes, const uint1
                 const double *x = Xd + m * K;
                 for (int64_t k = 0; k < K; k++) acc += x[k] * wrow[k];
                 Y[m * N + n] = S * acc;
+            }
+        }
+        free(wrow);
+    }
+    free(Xd);
+}
+
+/* ------------------------------------------------ fine-grained (block-k) scales */
+
+/*
+ * Fine-grained quantization (Section 3, "FGQ"; Appendix A, "block-k quantization: for
+ * every k elements, they have their own scaling factor"): a row of W is cut into blocks
+ * of `block` consecutive elements along K, and each block is quantized exactly like a
+ * whole row above, with its own S = RNE_fp16(max|w| / 28) (Eq. 3).  block == K is the
+ * row-wise scheme.  Logical shapes: codes [N,K]; scales [N, K/block] row-major.
+ */
+int fp6o_quantize_fgq(const uint16_t *W, int64_t N, int64_t K, int64_t block, uint8_t *codes, uint16_t *scales)
+{
+    if (!W || !codes || !scales || N < 0 || K < 0 || block <= 0 || K % block != 0) return FP6O_ERR_ARG;
+    const int64_t G = K / block;
+    int status = FP6O_OK;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; n++) {
+        for (int64_t g = 0; g < G; g++) {
+            const uint16_t *w = W + n * K + g * block;
+            uint16_t S;
+            if (fp6o_row_scale(w, block, &S) != FP6O_OK) {
+#pragma omp atomic write
+                status = FP6O_ERR_NONFINITE;
+                continue;
+            }
+            scales[n * G + g] = S;
+            int64_t s_units = half_abs_units(S);
+            for (int64_t k = 0; k < block; k++) {
+                int c5 = nearest_mag_code(half_abs_units(w[k]), s_units);
+                codes[n * K + g * block + k] = (uint8_t)(((w[k] >> 15) << 5) | c5);
+            }
+        }
+    }
+    return status;
+}
+
+/* W_hat[n,k] = RNE_fp16( S[n, k/block] * value(code) ) */
+void fp6o_dequantize_fgq(const uint8_t *codes, const uint16_t *scales, int64_t N, int64_t K, int64_t block,
+                         uint16_t *W_hat)
+{
+    const int64_t G = K / block;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; n++) {
+        for (int64_t k = 0; k < K; k++) {
+            int64_t s_units = half_abs_units(scales[n * G + k / block]);
+            int c = codes[n * K + k];
+            uint16_t mag = round_units_to_half(s_units * (int64_t)mag16(c & 31), 16);
+            W_hat[n * K + k] = (uint16_t)(((c >> 5) << 15) | mag);
+        }
+    }
+}
+
+/* Y[m,n] = sum_g S[n,g] * ( sum_{k in block g} X[m,k] * value(code[n,k]) ): the scale
+ * multiplies each block's product sum before the blocks are accumulated (Section 5.2,
+ * fine-grained case).  Double precision throughout. */
+void fp6o_linear_fgq(const uint16_t *X, int64_t M, const uint8_t *codes, const uint16_t *scales,
+                     int64_t N, int64_t K, int64_t block, double *Y)
+{
+    const int64_t G = K / block;
+    double *Xd = (double *)malloc(sizeof(double) * (size_t)(M * K > 0 ? M * K : 1));
+    for (int64_t i = 0; i < M * K; i++) Xd[i] = fp6o_half_to_double(X[i]);
+#pragma omp parallel
+    {
+        double *wrow = (double *)malloc(sizeof(double) * (size_t)(K > 0 ? K : 1));
+#pragma omp for schedule(static)
+        for (int64_t n = 0; n < N; n++) {
+            for (int64_t k = 0; k < K; k++) wrow[k] = fp6o_e3m2_value(codes[n * K + k]);
+            for (int64_t m = 0; m < M; m++) {
+                const double *x = Xd + m * K;
+                double y = 0.0;
+                for (int64_t g = 0; g < G; g++) {
+                    double acc = 0.0;
+                    for (int64_t k = g * block; k < (g + 1) * block; k++) acc += x[k] * wrow[k];
+                    y += fp6o_half_to_double(scales[n * G + g]) * acc;
+                }
+                Y[m * N + n] = y;
             }
         }
         free(wrow);

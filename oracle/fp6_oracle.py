@@ -40,6 +40,12 @@ def lib() -> ctypes.CDLL:
         L.fp6o_dequantize.argtypes = [p, p, i64, i64, p]
         L.fp6o_linear.restype = None
         L.fp6o_linear.argtypes = [p, i64, p, p, i64, i64, p]
+        L.fp6o_quantize_fgq.restype = ctypes.c_int
+        L.fp6o_quantize_fgq.argtypes = [p, i64, i64, i64, p, p]
+        L.fp6o_dequantize_fgq.restype = None
+        L.fp6o_dequantize_fgq.argtypes = [p, p, i64, i64, i64, p]
+        L.fp6o_linear_fgq.restype = None
+        L.fp6o_linear_fgq.argtypes = [p, i64, p, p, i64, i64, i64, p]
         L.fp6o_threads.restype = ctypes.c_int
         L.fp6o_threads.argtypes = []
         _LIB = L
@@ -140,4 +146,45 @@ def linear(X, codes, scales) -> np.ndarray:
     assert K == K2 and scales.size == N
     Y = np.zeros((M, N), np.float64)
     lib().fp6o_linear(_ptr(X), M, _ptr(codes), _ptr(scales), N, K, _ptr(Y))
+    return Y
+
+
+# ---- fine-grained (block-k) scales: Section 3 "FGQ", Appendix A "block-k quantization"
+
+def quantize_fgq(W, block: int):
+    """W fp16 [N,K] -> (codes uint8 [N,K], scales uint16 fp16-bits [N, K/block])."""
+    W = _bits(W)
+    if W.ndim != 2:
+        raise ValueError("W must be [N,K]")
+    N, K = W.shape
+    if block <= 0 or K % block:
+        raise ValueError("block must divide K")
+    codes = np.zeros((N, K), np.uint8)
+    scales = np.zeros((N, K // block), np.uint16)
+    st = lib().fp6o_quantize_fgq(_ptr(W), N, K, block, _ptr(codes), _ptr(scales))
+    if st != 0:
+        raise ValueError("oracle: quantize_fgq failed (status %d)" % st)
+    return codes, scales
+
+
+def dequantize_fgq(codes, scales, block: int) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = _bits(scales)
+    N, K = codes.shape
+    assert scales.shape == (N, K // block)
+    out = np.zeros((N, K), np.uint16)
+    lib().fp6o_dequantize_fgq(_ptr(codes), _ptr(scales), N, K, block, _ptr(out))
+    return out
+
+
+def linear_fgq(X, codes, scales, block: int) -> np.ndarray:
+    """X fp16 [M,K]; codes [N,K]; scales fp16 [N,K/block] -> Y float64 [M,N]."""
+    X = _bits(X)
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = _bits(scales)
+    M, K = X.shape
+    N, K2 = codes.shape
+    assert K == K2 and scales.shape == (N, K // block)
+    Y = np.zeros((M, N), np.float64)
+    lib().fp6o_linear_fgq(_ptr(X), M, _ptr(codes), _ptr(scales), N, K, block, _ptr(Y))
     return Y

@@ -359,3 +359,93 @@ def test_linear_scale_applies_after_the_sum_and_uses_true_code_values():
     Y = O.linear(np.array([[1.0]], np.float16), codes, S.view(np.uint16))
     assert Y[0, 0] == float(S[0]) * 7.0
     assert float(np.float16(Y[0, 0])) != Y[0, 0]
+
+
+# ------------------------------------------------------------------ fine-grained (block-k) scales
+
+def _rows(rng, N, K, sigma=0.02):
+    W = (rng.standard_normal((N, K)) * sigma).astype(np.float16)
+    W[rng.random((N, K)) < 0.002] *= np.float16(10.0)
+    return W
+
+
+def test_fgq_with_block_equal_to_row_is_the_row_wise_scheme():
+    # Section 3: coarse-grained = block size equal to the row size
+    rng = np.random.default_rng(21)
+    W = _rows(rng, 6, 192)
+    c1, s1 = O.quantize(W)
+    c2, s2 = O.quantize_fgq(W, 192)
+    assert np.array_equal(c1, c2) and np.array_equal(s1, s2[:, 0])
+    X = rng.standard_normal((3, 192)).astype(np.float16)
+    assert np.array_equal(O.linear(X, c1, s1), O.linear_fgq(X, c2, s2, 192))
+    assert np.array_equal(O.dequantize(c1, s1), O.dequantize_fgq(c2, s2, 192))
+
+
+def test_fgq_every_block_is_an_independent_row():
+    # block-k quantization: every k elements have their own scale (Appendix A) - so quantizing
+    # the [N, K] matrix in blocks equals quantizing the [N*K/block, block] matrix row-wise
+    rng = np.random.default_rng(22)
+    N, K = 5, 512
+    W = _rows(rng, N, K)
+    for block in (64, 128, 256):
+        c, s = O.quantize_fgq(W, block)
+        cr, sr = O.quantize(W.reshape(N * K // block, block))
+        assert np.array_equal(c.reshape(-1, block), cr)
+        assert np.array_equal(s.reshape(-1), sr)
+        # each block's largest element sits on the largest code, and the scale is max/28 rounded once
+        a = np.abs(W.astype(np.float64)).reshape(N, K // block, block)
+        assert np.array_equal(s.view(np.float16), (a.max(axis=2) / 28.0).astype(np.float16))
+        top = np.take_along_axis((c & 31).reshape(N, K // block, block), a.argmax(axis=2)[..., None], axis=2)
+        assert np.all(top == 31)
+        # finer blocks never quantize worse than coarser ones in the block's own max-norm bound
+        err = np.abs(O.dequantize_fgq(c, s, block).view(np.float16).astype(np.float64) - W.astype(np.float64))
+        bound = 2.0 * s.view(np.float16).astype(np.float64).repeat(block, axis=1) * (1 + 2.0 ** -10) + 2.0 ** -24
+        assert np.all(err <= bound)
+
+
+def test_fgq_dequantize_uses_the_scale_of_the_elements_own_block():
+    codes = np.tile(np.arange(64, dtype=np.uint8), (2, 4))           # K = 256, every code in every block
+    scales = np.array([[0.5, 0.25, 2.0, 0.0078125], [1.0, 4.0, 0.125, 0.03125]], np.float16)
+    got = O.dequantize_fgq(codes, scales.view(np.uint16), 64).view(np.float16).astype(np.float64)
+    vals = np.array([MAGS[c & 31] * (-1 if c & 32 else 1) for c in range(64)])
+    for n in range(2):
+        for g in range(4):
+            assert np.array_equal(got[n, 64 * g:64 * (g + 1)], float(scales[n, g]) * vals)
+
+
+def test_fgq_linear_bruteforce_fractions_tiny():
+    rng = np.random.default_rng(23)
+    M, N, K, block = 2, 3, 12, 4
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    codes = rng.integers(0, 64, (N, K), dtype=np.uint8)
+    scales = rng.integers(0x1000, 0x3C00, (N, K // block)).astype(np.uint16)
+    Y = O.linear_fgq(X, codes, scales, block)
+    for m in range(M):
+        for n in range(N):
+            exact = Fraction(0)
+            for k in range(K):
+                S = Fraction(float(scales[n, k // block:k // block + 1].view(np.float16)[0]))
+                exact += S * Fraction(float(X[m, k])) * Fraction(MAGS[codes[n, k] & 31]) * (-1 if codes[n, k] & 32 else 1)
+            assert abs(Y[m, n] - float(exact)) <= 1e-13 * max(1.0, abs(float(exact)))
+
+
+def test_fgq_linear_equals_numpy_matmul_when_everything_is_exact():
+    # small integers and power-of-two scales: every product, block sum and total is exact in
+    # double, so the definition must equal numpy's float64 matmul on the scaled weights
+    rng = np.random.default_rng(24)
+    M, N, K, block = 4, 5, 256, 64
+    X = rng.integers(-8, 9, (M, K)).astype(np.float16)
+    codes = rng.integers(0, 64, (N, K), dtype=np.uint8)
+    scales = (2.0 ** rng.integers(-6, 3, (N, K // block))).astype(np.float16)
+    Wv = np.array([[MAGS[c & 31] * (-1 if c & 32 else 1) for c in row] for row in codes])
+    Ws = Wv * scales.astype(np.float64).repeat(block, axis=1)
+    assert np.array_equal(O.linear_fgq(X, codes, scales.view(np.uint16), block), X.astype(np.float64) @ Ws.T)
+
+
+def test_fgq_linear_scale_multiplies_the_block_sum_not_the_rounded_weight():
+    # S * 7 needs 13 significant bits: the exact product must survive (no fp16 rounding of S*v)
+    S = np.array([[0.0999755859375, 0.5]], np.float16)
+    codes = np.array([[23, 0, 0, 0, 12, 12, 12, 12]], np.uint8)
+    X = np.array([[1, 0, 0, 0, 1, 1, 1, 1]], np.float16)
+    Y = O.linear_fgq(X, codes, S.view(np.uint16), 4)
+    assert Y[0, 0] == float(S[0, 0]) * 7.0 + 0.5 * 4.0
