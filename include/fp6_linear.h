@@ -179,6 +179,32 @@ int fp6_linear_variant(const uint16_t *X, int64_t M, const void *hi_plane, const
                        void *workspace, size_t workspace_bytes, void *stream,
                        int variant, int split_k);
 
+/*
+ * Fine-grained quantization (Section 3, "FGQ"; Appendix A, block-k quantization): every
+ * `block` consecutive elements of a row of W share one scale, S = RNE_fp16(max|w| / 28)
+ * over the block (Eq. 3), instead of one scale per row.  In the linear layer the scale
+ * multiplies the product sum of its block before the blocks are accumulated (Section 5.2,
+ * fine-grained case):
+ *     Y[m,n] = fp16( 2^12 * sum_g float(S[n,g]) * ( sum_{k in block g} X[m,k] * h(code[n,k]) ) )
+ * with fp32 accumulation inside and across blocks.
+ *   block   64, 128, 256, ... (64 times a power of two), dividing K
+ *   scales  device, fp16 bits, K/block * N of them; the scale of row n, block g is
+ *           scales[g * N + n] (block-major: neighbouring channels are neighbours in memory)
+ * Planes, codes and every other convention are those of the row-wise calls above;
+ * fp6_unpack_codes serves both.  `variant` and `split_k` as in fp6_linear_variant (0, 0 =
+ * automatic); the hints FP6_HINT_WAVES, FP6_HINT_DEPTH, FP6_HINT_DEQUANT and a block_m
+ * above 64 are not available with fine-grained scales.
+ */
+int fp6_quantize_pack_fgq(const uint16_t *W, int64_t N, int64_t K, int64_t block, void *hi_plane,
+                          void *lo_plane, uint16_t *scales, void *stream);
+int fp6_dequantize_fgq(const void *hi_plane, const void *lo_plane, const uint16_t *scales,
+                       int64_t N, int64_t K, int64_t block, uint16_t *W_hat, void *stream);
+size_t fp6_linear_fgq_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t block, int variant,
+                                      int split_k);
+int fp6_linear_fgq(const uint16_t *X, int64_t M, const void *hi_plane, const void *lo_plane,
+                   const uint16_t *scales, int64_t N, int64_t K, int64_t block, uint16_t *Y,
+                   void *workspace, size_t workspace_bytes, void *stream, int variant, int split_k);
+
 #ifdef __cplusplus
 }
 #endif

@@ -4,4 +4,5 @@ from .binding import (  # noqa: F401
     fp6_dequantize, fp6_layout_version, fp6_linear, fp6_linear_variant,
     fp6_linear_variant_workspace_bytes, fp6_linear_workspace_bytes, fp6_packed_sizes,
     fp6_quantize_pack, fp6_status_string, fp6_unpack_codes, new_workspace,
+    fp6_dequantize_fgq, fp6_linear_fgq, fp6_linear_fgq_workspace_bytes, fp6_quantize_pack_fgq,
 )

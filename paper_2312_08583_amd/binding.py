@@ -43,7 +43,8 @@ def FP6_HINT_DEQUANT(x: int) -> int:
 
 EXPORTS = ["fp6_layout_version", "fp6_status_string", "fp6_packed_sizes", "fp6_quantize_pack",
            "fp6_unpack_codes", "fp6_dequantize", "fp6_linear_workspace_bytes", "fp6_linear",
-           "fp6_linear_variant_workspace_bytes", "fp6_linear_variant"]
+           "fp6_linear_variant_workspace_bytes", "fp6_linear_variant", "fp6_quantize_pack_fgq",
+           "fp6_dequantize_fgq", "fp6_linear_fgq_workspace_bytes", "fp6_linear_fgq"]
 
 _LIB = None
 
@@ -82,6 +83,14 @@ def lib() -> ctypes.CDLL:
     L.fp6_linear_variant_workspace_bytes.argtypes = [i64, i64, i64, ci, ci]
     L.fp6_linear_variant.restype = ci
     L.fp6_linear_variant.argtypes = [p, i64, p, p, p, i64, i64, p, p, sz, p, ci, ci]
+    L.fp6_quantize_pack_fgq.restype = ci
+    L.fp6_quantize_pack_fgq.argtypes = [p, i64, i64, i64, p, p, p, p]
+    L.fp6_dequantize_fgq.restype = ci
+    L.fp6_dequantize_fgq.argtypes = [p, p, p, i64, i64, i64, p, p]
+    L.fp6_linear_fgq_workspace_bytes.restype = sz
+    L.fp6_linear_fgq_workspace_bytes.argtypes = [i64, i64, i64, i64, ci, ci]
+    L.fp6_linear_fgq.restype = ci
+    L.fp6_linear_fgq.argtypes = [p, i64, p, p, p, i64, i64, i64, p, p, sz, p, ci, ci]
     _LIB = L
     return L
 
@@ -197,4 +206,55 @@ def fp6_linear(X: torch.Tensor, hi: torch.Tensor, lo: torch.Tensor, scales: torc
     _check(lib().fp6_linear(xp, M, _dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"),
                             _dev(scales, torch.float16, "scales"), N, K, _dev(out, torch.float16, "Y"),
                             wp, wb, _stream()), "fp6_linear")
+    return out
+
+
+# ---- fine-grained (block-k) scales
+
+def fp6_quantize_pack_fgq(W: torch.Tensor, block: int):
+    """W fp16 [N,K] -> (hi_plane, lo_plane, scales fp16 [K/block, N]): one scale per `block` elements of a row."""
+    wp = _dev(W, torch.float16, "W")
+    N, K = W.shape
+    hb, lb, _ = fp6_packed_sizes(N, K)
+    if block <= 0 or K % block:
+        raise Fp6Error("block must divide K")
+    hi = torch.empty(hb, dtype=torch.uint8, device=W.device)
+    lo = torch.empty(lb, dtype=torch.uint8, device=W.device)
+    scales = torch.empty((K // block, N), dtype=torch.float16, device=W.device)
+    _check(lib().fp6_quantize_pack_fgq(wp, N, K, block, hi.data_ptr(), lo.data_ptr(), scales.data_ptr(), _stream()),
+           "fp6_quantize_pack_fgq")
+    return hi, lo, scales
+
+
+def fp6_dequantize_fgq(hi: torch.Tensor, lo: torch.Tensor, scales: torch.Tensor, N: int, K: int,
+                       block: int) -> torch.Tensor:
+    out = torch.empty((N, K), dtype=torch.float16, device=hi.device)
+    _check(lib().fp6_dequantize_fgq(_dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"),
+                                    _dev(scales, torch.float16, "scales"), N, K, block, out.data_ptr(), _stream()),
+           "fp6_dequantize_fgq")
+    return out
+
+
+def fp6_linear_fgq_workspace_bytes(M: int, N: int, K: int, block: int, variant: int = FP6_VARIANT_AUTO,
+                                   split_k: int = 0) -> int:
+    return int(lib().fp6_linear_fgq_workspace_bytes(M, N, K, block, variant, split_k))
+
+
+def fp6_linear_fgq(X: torch.Tensor, hi: torch.Tensor, lo: torch.Tensor, scales: torch.Tensor, N: int, K: int,
+                   block: int, variant: int = FP6_VARIANT_AUTO, split_k: int = 0,
+                   out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Y[M,N] with block scales applied to each block's product sum before the accumulation."""
+    xp = _dev(X, torch.float16, "X")
+    M = X.shape[0]
+    if X.dim() != 2 or X.shape[1] != K:
+        raise Fp6Error("X must be [M,K]")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    if workspace is None:
+        workspace = new_workspace(fp6_linear_fgq_workspace_bytes(M, N, K, block, variant, split_k), X.device)
+    wp = workspace.data_ptr() if workspace is not None else None
+    wb = workspace.numel() if workspace is not None else 0
+    _check(lib().fp6_linear_fgq(xp, M, _dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"),
+                                _dev(scales, torch.float16, "scales"), N, K, block, _dev(out, torch.float16, "Y"),
+                                wp, wb, _stream(), variant, split_k), "fp6_linear_fgq")
     return out

@@ -32,7 +32,13 @@ static int pick_decode_split(int64_t units, int64_t ktiles, int waves)
     return best;
 }
 
-bool make_plan(int64_t M, int64_t N, int64_t K, int variant, int split_k, LinearPlan* plan)
+// fine-grained blocks: 64 * 2^j elements, dividing K
+static bool block_ok(int64_t K, int64_t block)
+{
+    return block >= FP6_TILE && block % FP6_TILE == 0 && ((block / FP6_TILE) & (block / FP6_TILE - 1)) == 0 && K % block == 0;
+}
+
+bool make_plan(int64_t M, int64_t N, int64_t K, int64_t block, int variant, int split_k, LinearPlan* plan)
 {
     const int64_t ktiles = K / FP6_TILE, nblocks = N / FP6_TILE;
     // tuning hints ride in the upper bits of `variant`; 0 = automatic
@@ -47,6 +53,11 @@ bool make_plan(int64_t M, int64_t N, int64_t K, int variant, int split_k, Linear
     LinearPlan p{};
     p.variant = variant;
     p.dequant = hint_dequant;
+    p.gshift = -1;
+    if (block) {
+        if (!block_ok(K, block) || hint_dequant || hint_waves || hint_depth) return false;
+        for (int64_t b = block / FP6_TILE; b; b >>= 1) p.gshift++;
+    }
     // the ablations exist for the default kernel configurations only
     if (hint_dequant > 2 || (hint_dequant && (hint_waves || hint_depth))) return false;
     int64_t tiles, regs_per_tile;
@@ -60,6 +71,17 @@ bool make_plan(int64_t M, int64_t N, int64_t K, int variant, int split_k, Linear
         tiles = nblocks;
         regs_per_tile = 256;                       // float4 per output tile (64 x 16 fp32)
         p.split_k = split_k ? split_k : pick_decode_split(nblocks, ktiles, p.waves);
+        if (block) {
+            // the scales of a workgroup's K-slice are staged in LDS, 128 bytes per block of K: keep that under 96 KB
+            auto lds = [&](int64_t d) { return (((ktiles / d - 1) >> p.gshift) + 2) * 128; };
+            if (lds(p.split_k) > 96 * 1024) {
+                if (split_k) return false;
+                int64_t d = p.split_k;
+                while (d <= ktiles && (ktiles % d || lds(d) > 96 * 1024)) d++;
+                if (d > ktiles) return false;
+                p.split_k = (int)d;
+            }
+        }
     } else {
         if ((hint_waves && hint_waves != 4 && hint_waves != 8) || hint_depth || hint_meet ||
             (hint_bm && hint_bm != 32 && hint_bm != 64 && hint_bm != 128))
@@ -72,7 +94,8 @@ bool make_plan(int64_t M, int64_t N, int64_t K, int variant, int split_k, Linear
         // block size (or of the HBM stream, whichever is longer) plus a fixed part that grows with
         // the number of slices the last workgroup of a tile has to add up.
         double best_cost = 0.0;
-        for (int bm = 32; bm <= 128; bm *= 2) {
+        if (block && hint_bm > 64) return false;        // fine-grained scales: two accumulators per tile
+        for (int bm = 32; bm <= (block ? 64 : 128); bm *= 2) {
             if (hint_bm ? bm != hint_bm : (bm > 32 && bm / 2 >= M)) continue;
             const int64_t mblk = (M + bm - 1) / bm, t = mblk * ((nblocks + 7) / 8);
             const double step = bm == 128 ? 1.47 : (bm == 64 ? 1.0 : 0.8);
@@ -123,6 +146,57 @@ static size_t plan_workspace(const LinearPlan& p) { return p.split_k > 1 ? kZero
 
 using namespace fp6;
 
+// block == 0: one scale per row
+static int quantize_pack_any(const uint16_t* W, int64_t N, int64_t K, int64_t block, void* hi_plane, void* lo_plane,
+                             uint16_t* scales, void* stream)
+{
+    if (!W || !hi_plane || !lo_plane || !scales) return FP6_ERR_NULL;
+    if (!shape_ok(N, K) || (block && !block_ok(K, block))) return FP6_ERR_SHAPE;
+    if (!aligned16(W) || !aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(scales)) return FP6_ERR_ALIGN;
+    return launch_quantize_pack(W, N, K, block ? block : K, hi_plane, lo_plane, scales, (hipStream_t)stream) ==
+                   hipSuccess
+               ? FP6_OK
+               : FP6_ERR_HIP;
+}
+
+static int dequantize_any(const void* hi_plane, const void* lo_plane, const uint16_t* scales, int64_t N, int64_t K,
+                          int64_t block, uint16_t* W_hat, void* stream)
+{
+    if (!hi_plane || !lo_plane || !scales || !W_hat) return FP6_ERR_NULL;
+    if (!shape_ok(N, K) || (block && !block_ok(K, block))) return FP6_ERR_SHAPE;
+    if (!aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(scales) || !aligned16(W_hat)) return FP6_ERR_ALIGN;
+    return launch_dequantize(hi_plane, lo_plane, scales, N, K, block ? block : K, W_hat, (hipStream_t)stream) ==
+                   hipSuccess
+               ? FP6_OK
+               : FP6_ERR_HIP;
+}
+
+static size_t workspace_any(int64_t M, int64_t N, int64_t K, int64_t block, int variant, int split_k)
+{
+    LinearPlan p;
+    if (M <= 0 || M > (int64_t)1 << 24 || !shape_ok(N, K) || !make_plan(M, N, K, block, variant, split_k, &p)) return 0;
+    return plan_workspace(p);
+}
+
+static int linear_any(const uint16_t* X, int64_t M, const void* hi_plane, const void* lo_plane,
+                      const uint16_t* scales, int64_t N, int64_t K, int64_t block, uint16_t* Y, void* workspace,
+                      size_t workspace_bytes, void* stream, int variant, int split_k)
+{
+    if (!X || !hi_plane || !lo_plane || !scales || !Y) return FP6_ERR_NULL;
+    if (M <= 0 || M > (int64_t)1 << 24 || !shape_ok(N, K) || block < 0) return FP6_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(scales) || !aligned16(Y) ||
+        !aligned16(workspace))
+        return FP6_ERR_ALIGN;
+    LinearPlan p;
+    if (!make_plan(M, N, K, block, variant, split_k, &p)) return FP6_ERR_VARIANT;
+    const size_t need = plan_workspace(p);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return FP6_ERR_WORKSPACE;
+    hipError_t e = (p.variant == FP6_VARIANT_DECODE)
+                       ? launch_decode(p, X, M, hi_plane, lo_plane, scales, N, K, Y, workspace, (hipStream_t)stream)
+                       : launch_gemm(p, X, M, hi_plane, lo_plane, scales, N, K, Y, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? FP6_OK : FP6_ERR_HIP;
+}
+
 extern "C" {
 
 int fp6_layout_version(void) { return FP6_LAYOUT_VERSION; }
@@ -153,11 +227,14 @@ int fp6_packed_sizes(int64_t N, int64_t K, size_t* hi_bytes, size_t* lo_bytes, s
 int fp6_quantize_pack(const uint16_t* W, int64_t N, int64_t K, void* hi_plane, void* lo_plane, uint16_t* scales,
                       void* stream)
 {
-    if (!W || !hi_plane || !lo_plane || !scales) return FP6_ERR_NULL;
-    if (!shape_ok(N, K)) return FP6_ERR_SHAPE;
-    if (!aligned16(W) || !aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(scales)) return FP6_ERR_ALIGN;
-    return launch_quantize_pack(W, N, K, hi_plane, lo_plane, scales, (hipStream_t)stream) == hipSuccess ? FP6_OK
-                                                                                                        : FP6_ERR_HIP;
+    return quantize_pack_any(W, N, K, 0, hi_plane, lo_plane, scales, stream);
+}
+
+int fp6_quantize_pack_fgq(const uint16_t* W, int64_t N, int64_t K, int64_t block, void* hi_plane, void* lo_plane,
+                          uint16_t* scales, void* stream)
+{
+    if (block <= 0) return FP6_ERR_SHAPE;
+    return quantize_pack_any(W, N, K, block, hi_plane, lo_plane, scales, stream);
 }
 
 int fp6_unpack_codes(const void* hi_plane, const void* lo_plane, int64_t N, int64_t K, uint8_t* codes, void* stream)
@@ -172,50 +249,53 @@ int fp6_unpack_codes(const void* hi_plane, const void* lo_plane, int64_t N, int6
 int fp6_dequantize(const void* hi_plane, const void* lo_plane, const uint16_t* scales, int64_t N, int64_t K,
                    uint16_t* W_hat, void* stream)
 {
-    if (!hi_plane || !lo_plane || !scales || !W_hat) return FP6_ERR_NULL;
-    if (!shape_ok(N, K)) return FP6_ERR_SHAPE;
-    if (!aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(scales) || !aligned16(W_hat)) return FP6_ERR_ALIGN;
-    return launch_dequantize(hi_plane, lo_plane, scales, N, K, W_hat, (hipStream_t)stream) == hipSuccess
-               ? FP6_OK
-               : FP6_ERR_HIP;
+    return dequantize_any(hi_plane, lo_plane, scales, N, K, 0, W_hat, stream);
+}
+
+int fp6_dequantize_fgq(const void* hi_plane, const void* lo_plane, const uint16_t* scales, int64_t N, int64_t K,
+                       int64_t block, uint16_t* W_hat, void* stream)
+{
+    if (block <= 0) return FP6_ERR_SHAPE;
+    return dequantize_any(hi_plane, lo_plane, scales, N, K, block, W_hat, stream);
 }
 
 size_t fp6_linear_variant_workspace_bytes(int64_t M, int64_t N, int64_t K, int variant, int split_k)
 {
-    LinearPlan p;
-    if (M <= 0 || M > (int64_t)1 << 24 || !shape_ok(N, K) || !make_plan(M, N, K, variant, split_k, &p)) return 0;
-    return plan_workspace(p);
+    return workspace_any(M, N, K, 0, variant, split_k);
 }
 
 size_t fp6_linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
-    return fp6_linear_variant_workspace_bytes(M, N, K, FP6_VARIANT_AUTO, 0);
+    return workspace_any(M, N, K, 0, FP6_VARIANT_AUTO, 0);
+}
+
+size_t fp6_linear_fgq_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t block, int variant, int split_k)
+{
+    return block > 0 ? workspace_any(M, N, K, block, variant, split_k) : 0;
 }
 
 int fp6_linear_variant(const uint16_t* X, int64_t M, const void* hi_plane, const void* lo_plane,
                        const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                        size_t workspace_bytes, void* stream, int variant, int split_k)
 {
-    if (!X || !hi_plane || !lo_plane || !scales || !Y) return FP6_ERR_NULL;
-    if (M <= 0 || M > (int64_t)1 << 24 || !shape_ok(N, K)) return FP6_ERR_SHAPE;
-    if (!aligned16(X) || !aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(scales) || !aligned16(Y) ||
-        !aligned16(workspace))
-        return FP6_ERR_ALIGN;
-    LinearPlan p;
-    if (!make_plan(M, N, K, variant, split_k, &p)) return FP6_ERR_VARIANT;
-    const size_t need = plan_workspace(p);
-    if (need > 0 && (!workspace || workspace_bytes < need)) return FP6_ERR_WORKSPACE;
-    hipError_t e = (p.variant == FP6_VARIANT_DECODE)
-                       ? launch_decode(p, X, M, hi_plane, lo_plane, scales, N, K, Y, workspace, (hipStream_t)stream)
-                       : launch_gemm(p, X, M, hi_plane, lo_plane, scales, N, K, Y, workspace, (hipStream_t)stream);
-    return e == hipSuccess ? FP6_OK : FP6_ERR_HIP;
+    return linear_any(X, M, hi_plane, lo_plane, scales, N, K, 0, Y, workspace, workspace_bytes, stream, variant,
+                      split_k);
 }
 
 int fp6_linear(const uint16_t* X, int64_t M, const void* hi_plane, const void* lo_plane, const uint16_t* scales,
                int64_t N, int64_t K, uint16_t* Y, void* workspace, size_t workspace_bytes, void* stream)
 {
-    return fp6_linear_variant(X, M, hi_plane, lo_plane, scales, N, K, Y, workspace, workspace_bytes, stream,
-                              FP6_VARIANT_AUTO, 0);
+    return linear_any(X, M, hi_plane, lo_plane, scales, N, K, 0, Y, workspace, workspace_bytes, stream,
+                      FP6_VARIANT_AUTO, 0);
+}
+
+int fp6_linear_fgq(const uint16_t* X, int64_t M, const void* hi_plane, const void* lo_plane, const uint16_t* scales,
+                   int64_t N, int64_t K, int64_t block, uint16_t* Y, void* workspace, size_t workspace_bytes,
+                   void* stream, int variant, int split_k)
+{
+    if (block <= 0) return FP6_ERR_SHAPE;
+    return linear_any(X, M, hi_plane, lo_plane, scales, N, K, block, Y, workspace, workspace_bytes, stream, variant,
+                      split_k);
 }
 
 }  // extern "C"

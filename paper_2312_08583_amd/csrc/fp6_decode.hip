@@ -45,12 +45,18 @@ __device__ __forceinline__ void tile_mac(const TileRaw& r, const XFrag& x, float
 
 // D = depth of the per-wavefront ring of tiles in flight (D-1 tiles are being fetched
 // while one is consumed).  The ring is indexed with compile-time constants only.
-template <int WAVES, int D, int DQ>
+// FGQ: one scale per `64 << gshift` elements along K (Section 3, fine-grained quantization)
+// instead of one per row.  A tile lies inside one such block, so its product sums are
+// formed in a zeroed accumulator and multiplied by the block's scales while they are added
+// to the running sum - "after matrix multiplication, before the accumulation" (Section 5.2).
+// The scales of the workgroup's 64 channels for its whole K-slice (128 bytes per block) are
+// copied to LDS first, while the first tiles are already on their way.
+template <int WAVES, int D, int DQ, bool FGQ>
 __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
     const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
     float4v* __restrict__ partials, uint32_t* __restrict__ counters, unsigned long long* __restrict__ slots,
-    int split_k, int pairwise)
+    int split_k, int pairwise, int gshift)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int ktiles = K / kTile;
@@ -63,12 +69,33 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     const size_t tile0 = (size_t)nb * ktiles;
 
     // row scales of the four channels this thread will store (fetched early: the epilogue is latency-bound)
-    half4 sc = half4{0, 0, 0, 0};
-    if ((int)threadIdx.x < 16 * M) sc = *reinterpret_cast<const half4*>(scales + nb * kTile + (threadIdx.x & 15) * 4);
+    half4 sc = half4{1, 1, 1, 1};
+    if (!FGQ && (int)threadIdx.x < 16 * M) sc = *reinterpret_cast<const half4*>(scales + nb * kTile + (threadIdx.x & 15) * 4);
 
     float4v acc[4];
 #pragma unroll
     for (int t = 0; t < 4; t++) acc[t] = float4v{0.f, 0.f, 0.f, 0.f};
+
+    // FGQ: this workgroup's scales -> LDS (16-byte pieces; piece c = block group0 + c/8, channels 8*(c%8)..+7),
+    // four loads per thread in flight
+    extern __shared__ __align__(16) uint16_t gscale[];
+    const int group0 = (s * kt_per) >> gshift;
+    if (FGQ) {
+        constexpr int T = WAVES * 64;
+        const int pieces = (((kt_end - 1) >> gshift) - group0 + 1) * 8;
+        for (int c0 = threadIdx.x; c0 < pieces; c0 += 4 * T) {
+            u32x4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const int c = min(c0 + u * T, pieces - 1);
+                v[u] = *reinterpret_cast<const u32x4*>(scales + (size_t)(group0 + (c >> 3)) * N + nb * kTile + (c & 7) * 8);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; u++)
+                if (c0 + u * T < pieces) *reinterpret_cast<u32x4*>(gscale + (c0 + u * T) * 8) = v[u];
+        }
+        __syncthreads();
+    }
 
     // this wavefront's tiles: kt0, kt0 + WAVES, ...  (cnt of them, possibly none)
     const int kt0 = s * kt_per + wave;
@@ -76,6 +103,24 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     if (cnt > 0) {
         TileRaw raw[D];
         XFrag xf[D];
+        // k = the tile's index along K
+        auto mac = [&](int slot, int k) {
+            if (FGQ) {
+                float4v part[4];
+#pragma unroll
+                for (int t = 0; t < 4; t++) part[t] = float4v{0.f, 0.f, 0.f, 0.f};
+                tile_mac<DQ>(raw[slot], xf[slot], part);
+                const uint16_t* sg = gscale + ((k >> gshift) - group0) * kTile + g * 4;
+#pragma unroll
+                for (int t = 0; t < 4; t++) {
+                    const half4 sv = *reinterpret_cast<const half4*>(sg + 16 * t);
+#pragma unroll
+                    for (int r = 0; r < 4; r++) acc[t][r] += part[t][r] * (float)sv[r];
+                }
+            } else {
+                tile_mac<DQ>(raw[slot], xf[slot], acc);
+            }
+        };
 
         // prologue: tiles 0 .. D-2 (clamped: a short wavefront re-reads its last tile)
 #pragma unroll
@@ -92,7 +137,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
                 const int k = kt0 + (j0 + u + D - 1) * WAVES;
                 raw[(u + D - 1) % D] = load_tile(hi, lo, tile0 + k, lane);
                 xf[(u + D - 1) % D] = load_x(xrow, k);
-                tile_mac<DQ>(raw[u], xf[u], acc);
+                mac(u, kt0 + (j0 + u) * WAVES);
             }
         }
         // drain: the remaining (< 2D-1) tiles, refilling only while tiles are left
@@ -105,7 +150,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
                     raw[(v + D - 1) % D] = load_tile(hi, lo, tile0 + k, lane);
                     xf[(v + D - 1) % D] = load_x(xrow, k);
                 }
-                tile_mac<DQ>(raw[v % D], xf[v % D], acc);
+                mac(v % D, kt0 + j * WAVES);
             }
         }
     }
@@ -177,7 +222,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     }
 }
 
-template <int WAVES, int D, int DQ = kBiasShift>
+template <int WAVES, int D, int DQ = kBiasShift, bool FGQ = false>
 static hipError_t launch_decode_t(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
                                   const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                                   hipStream_t stream)
@@ -186,9 +231,11 @@ static hipError_t launch_decode_t(const LinearPlan& p, const uint16_t* X, int64_
     float4v* partials = reinterpret_cast<float4v*>(reinterpret_cast<char*>(workspace) + kZeroBytes);
     unsigned long long* slots = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(workspace) + kCounterBytes);
     const unsigned grid = (unsigned)((N / kTile) * p.split_k);
-    hipLaunchKernelGGL((decode_kernel<WAVES, D, DQ>), dim3(grid), dim3(WAVES * 64), 0, stream, X, (int)M,
+    // FGQ: 128 bytes of scales per block of K in a workgroup's slice (a slice may start inside a block)
+    const size_t lds = FGQ ? (size_t)(((K / kTile / p.split_k - 1) >> p.gshift) + 2) * 128 : 0;
+    hipLaunchKernelGGL((decode_kernel<WAVES, D, DQ, FGQ>), dim3(grid), dim3(WAVES * 64), lds, stream, X, (int)M,
                        (const u32x4*)hi, (const u32x4*)lo, scales, (int)N, (int)K, Y, partials, counters, slots,
-                       p.split_k, p.pairwise);
+                       p.split_k, p.pairwise, p.gshift);
     return hipGetLastError();
 }
 
@@ -196,6 +243,7 @@ hipError_t launch_decode(const LinearPlan& p, const uint16_t* X, int64_t M, cons
                          const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                          hipStream_t stream)
 {
+    if (p.gshift >= 0) return launch_decode_t<4, 4, kBiasShift, true>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     if (p.dequant == kIntRebias) return launch_decode_t<4, 4, kIntRebias>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     if (p.dequant == kHalfMul) return launch_decode_t<4, 4, kHalfMul>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     switch (p.waves * 10 + p.depth) {

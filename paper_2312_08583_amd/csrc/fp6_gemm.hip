@@ -52,6 +52,15 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t lane_offset, ui
                  : "memory");
 }
 
+// 4 bytes per lane from (base + lane_offset) to LDS address lds + 4 * lane.
+__device__ __forceinline__ void dma4(const void* base, uint32_t lane_offset, uint32_t lds)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 :
+                 : "v"(lane_offset), "s"(base), "s"(lds)
+                 : "memory");
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
@@ -59,21 +68,28 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
-template <int BM, int D, int WN, int DQ>
+// FGQ: one scale per `64 << gshift` elements along K (Section 3, fine-grained quantization).
+// The product sums of the k tiles of one such block are formed in a second accumulator; at
+// the end of the block they are multiplied by the block's scales and added to the running
+// sum - "after matrix multiplication, before the accumulation" (Section 5.2).  The scales of
+// a wavefront's 64 channels (128 bytes per block) ride along with every stage of the DMA ring.
+template <int BM, int D, int WN, int DQ, bool FGQ>
 __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
     const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
     const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
-    float4v* __restrict__ partials, uint32_t* __restrict__ counters, int split_k)
+    float4v* __restrict__ partials, uint32_t* __restrict__ counters, int split_k, int gshift)
 {
+    static_assert(!FGQ || (WN == 1 && BM <= 64), "fine-grained scales: two accumulators must fit the register file");
     constexpr int WAVES = kGemmBlocksN / WN;
     constexpr int THREADS = WAVES * 64;
     constexpr int MT = BM / 16;                         // 16-row blocks of X per workgroup
     constexpr int NT = 4 * WN;                          // 16-channel blocks per wavefront
     constexpr int XG = BM / 8;                          // 8-row groups (1 KB of DMA each) per stage
     constexpr int XL = XG >= WAVES ? XG / WAVES : 1;    // X groups moved per wavefront and k tile
-    constexpr int kLoads = XL + 3 * WN;                 // DMA instructions per wavefront and k tile
+    constexpr int kLoads = XL + 3 * WN + (FGQ ? 1 : 0); // DMA instructions per wavefront and k tile
     constexpr int kXBytes = BM * kTile * 2;
-    constexpr int kStageBytes = kXBytes + kGemmBlocksN * kWaveTileBytes;
+    constexpr int kScaleOff = kXBytes + kGemmBlocksN * kWaveTileBytes;     // FGQ: 256 bytes per wavefront
+    constexpr int kStageBytes = kScaleOff + (FGQ ? WAVES * 256 : 0);
     constexpr int kTileRegs = MT * NT * THREADS;        // float4 per output tile
     __shared__ __align__(16) unsigned char smem[D * kStageBytes];
 
@@ -142,6 +158,13 @@ __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
             dma16(hb + 1024, wlane, sb + wlds + c * kWaveTileBytes + 1024);
             dma16(lb, wlane, sb + wlds + c * kWaveTileBytes + 2048);
         }
+        if (FGQ) {
+            // scales of this tile's block for the wavefront's 64 channels: 128 bytes, fetched by lanes
+            // 0..31 (the upper lanes fetch the same bytes again rather than bytes past the array)
+            const unsigned char* sp = reinterpret_cast<const unsigned char*>(scales) +
+                                      ((size_t)(kt >> gshift) * N + (size_t)min(nb0, nblocks - 1) * kTile) * 2;
+            dma4(sp, (lane & 31) * 4, sb + kScaleOff + wave * 256);
+        }
     };
 
     // operand reads: row r = 16a + i, chunk 4q + g, at position (4q + g) ^ (i & 7)
@@ -149,10 +172,14 @@ __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
     const int xoff1 = i * (kTile * 2) + (((4 + g) ^ (i & 7)) * 16);
 
     float4v acc[MT][NT];
+    float4v part[FGQ ? MT : 1][FGQ ? NT : 1];      // FGQ: product sums of the current block of K
 #pragma unroll
     for (int a = 0; a < MT; a++)
 #pragma unroll
-        for (int t = 0; t < NT; t++) acc[a][t] = float4v{0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < NT; t++) {
+            acc[a][t] = float4v{0.f, 0.f, 0.f, 0.f};
+            if (FGQ) part[a][t] = float4v{0.f, 0.f, 0.f, 0.f};
+        }
 
 #pragma unroll
     for (int u = 0; u < D - 1; u++) issue(min(kt_begin + u, kt_end - 1), u);
@@ -184,7 +211,25 @@ __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
             for (int t = 0; t < NT; t++) {
                 half8 w = unpack_tile_fragment<DQ>(raw[t / 4], 2 * (t % 4) + q);
 #pragma unroll
-                for (int a = 0; a < MT; a++) acc[a][t] = mfma16x16x32(w, xf[a], acc[a][t]);
+                for (int a = 0; a < MT; a++) {
+                    if (FGQ) part[a][t] = mfma16x16x32(w, xf[a], part[a][t]);
+                    else acc[a][t] = mfma16x16x32(w, xf[a], acc[a][t]);
+                }
+            }
+        }
+        if (FGQ) {
+            // last tile of a block of K (or of this workgroup's K-slice): scale and accumulate
+            if ((((kt + 1) >> gshift) << gshift) == kt + 1 || kt + 1 == kt_end) {
+#pragma unroll
+                for (int t = 0; t < NT; t++) {
+                    const half4 h = *reinterpret_cast<const half4*>(st + kScaleOff + wave * 256 + (t * 16 + g * 4) * 2);
+#pragma unroll
+                    for (int a = 0; a < MT; a++) {
+#pragma unroll
+                        for (int r = 0; r < 4; r++) acc[a][t][r] += part[a][t][r] * (float)h[r];
+                        part[a][t] = float4v{0.f, 0.f, 0.f, 0.f};
+                    }
+                }
             }
         }
         // Issue order.  The wavefronts of a SIMD leave the barrier together, so they cannot hide
@@ -193,6 +238,7 @@ __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
         // shadow), and the LDS operand reads of the second k block are spread over the MFMAs of
         // the first.
 #if FP6_GEMM_HINTS
+        if (!FGQ) {
         __builtin_amdgcn_sched_group_barrier(0x100, 3 * WN + MT, 0);     // planes + operands of k block 0
         __builtin_amdgcn_sched_group_barrier(0x002, 15, 0);              // first fragment
 #pragma unroll
@@ -200,6 +246,7 @@ __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
             if (n % 2 == 0 && n >= NT * MT - 2 * MT && n < NT * MT) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
         }
 #endif
     };
@@ -268,7 +315,8 @@ __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
         float sc[4][4];
 #pragma unroll
         for (int t = 0; t < 4; t++) {
-            const half4 h = *reinterpret_cast<const half4*>(scales + (size_t)nb * kTile + t * 16 + g2 * 4);
+            half4 h = half4{1, 1, 1, 1};       // fine-grained scales were applied block by block
+            if (!FGQ) h = *reinterpret_cast<const half4*>(scales + (size_t)nb * kTile + t * 16 + g2 * 4);
 #pragma unroll
             for (int r = 0; r < 4; r++) sc[t][r] = (float)h[r] * kUnshift<DQ>;
         }
@@ -288,7 +336,7 @@ __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
     }
 }
 
-template <int BM, int D, int WN, int DQ = kBiasShift>
+template <int BM, int D, int WN, int DQ = kBiasShift, bool FGQ = false>
 static hipError_t launch_gemm_t(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
                                 const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                                 hipStream_t stream)
@@ -298,8 +346,8 @@ static hipError_t launch_gemm_t(const LinearPlan& p, const uint16_t* X, int64_t 
     const int64_t mblk = (M + BM - 1) / BM, nblk = (N / kTile + kGemmBlocksN - 1) / kGemmBlocksN;
     const unsigned grid = (unsigned)(nblk >= 8 ? mblk * ((nblk + 7) / 8 * 8) * p.split_k
                                                : mblk * ((nblk * p.split_k + 7) / 8 * 8));   // padded: see the id mapping
-    hipLaunchKernelGGL((gemm_kernel<BM, D, WN, DQ>), dim3(grid), dim3(kGemmBlocksN / WN * 64), 0, stream, X, (int)M,
-                       (const u32x4*)hi, (const u32x4*)lo, scales, (int)N, (int)K, Y, partials, counters, p.split_k);
+    hipLaunchKernelGGL((gemm_kernel<BM, D, WN, DQ, FGQ>), dim3(grid), dim3(kGemmBlocksN / WN * 64), 0, stream, X, (int)M,
+                       (const u32x4*)hi, (const u32x4*)lo, scales, (int)N, (int)K, Y, partials, counters, p.split_k, p.gshift);
     return hipGetLastError();
 }
 
@@ -307,6 +355,10 @@ hipError_t launch_gemm(const LinearPlan& p, const uint16_t* X, int64_t M, const 
                        const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                        hipStream_t stream)
 {
+    if (p.gshift >= 0) {
+        if (p.block_m == 32) return launch_gemm_t<32, 4, 1, kBiasShift, true>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        return launch_gemm_t<64, 4, 1, kBiasShift, true>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+    }
     switch (p.block_m * 10 + p.waves + p.dequant * 10000) {
         case 10328: return launch_gemm_t<32, 4, 1, kIntRebias>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
         case 10648: return launch_gemm_t<64, 4, 1, kIntRebias>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);

@@ -16,12 +16,13 @@ constexpr size_t kCounterBytes = (size_t)kMaxCounters * kCounterStride * sizeof(
 constexpr size_t kSlotBytes = (size_t)4 << 20;
 constexpr size_t kZeroBytes = kCounterBytes + kSlotBytes;
 
-hipError_t launch_quantize_pack(const uint16_t* W, int64_t N, int64_t K, void* hi, void* lo, uint16_t* scales,
-                                hipStream_t stream);
+// `block` = elements along K that share a scale (K itself for the row-wise scheme); scale (n, g) at scales[g*N + n]
+hipError_t launch_quantize_pack(const uint16_t* W, int64_t N, int64_t K, int64_t block, void* hi, void* lo,
+                                uint16_t* scales, hipStream_t stream);
 hipError_t launch_unpack_codes(const void* hi, const void* lo, int64_t N, int64_t K, uint8_t* codes,
                                hipStream_t stream);
 hipError_t launch_dequantize(const void* hi, const void* lo, const uint16_t* scales, int64_t N, int64_t K,
-                             uint16_t* W_hat, hipStream_t stream);
+                             int64_t block, uint16_t* W_hat, hipStream_t stream);
 
 // A fully resolved launch plan for fp6_linear.
 struct LinearPlan {
@@ -32,12 +33,14 @@ struct LinearPlan {
     int depth;          // tiles in the per-wavefront prefetch ring
     size_t partial_bytes;   // fp32 partial sums needed in the workspace (0 if split_k == 1)
     int counters;       // arrival counters used (0 if split_k == 1)
+    int gshift;         // fine-grained scales: log2(block / 64); -1 = one scale per row
     int dequant;        // 0: bias-shift unpack (the method); 1, 2: ablations (integer re-bias, fp16 multiply)
     int pairwise;       // DECODE with split_k > 1: K-slices meet pairwise in the slot region (1) or at a counter (0)
 };
 
 // Heuristic (or caller-forced) plan; returns false if the request is invalid for the shape.
-bool make_plan(int64_t M, int64_t N, int64_t K, int variant, int split_k, LinearPlan* plan);
+// `block` = elements along K per scale (0 = row-wise).
+bool make_plan(int64_t M, int64_t N, int64_t K, int64_t block, int variant, int split_k, LinearPlan* plan);
 
 hipError_t launch_decode(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
                          const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,

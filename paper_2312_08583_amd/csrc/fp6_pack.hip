@@ -5,19 +5,24 @@
 
 namespace fp6 {
 
-// ------------------------------------------------------------------ row scales
-// S_n = RNE_fp16(max_k |W[n,k]| / 28).  |w| of finite fp16 orders like its 15 magnitude
-// bits, so the maximum is taken on integers.  The quotient is one IEEE fp32 division
-// followed by one fp32->fp16 rounding; a double rounding cannot occur because amax/28
-// is either exact in fp16 or at least 2^-14 (relative) away from every fp16 midpoint.
-__global__ __launch_bounds__(256) void row_scale_kernel(const uint16_t* __restrict__ W, int64_t K,
-                                                         uint16_t* __restrict__ scales)
+// ------------------------------------------------------------------ scales
+// S = RNE_fp16(max |w| / 28) over one block of `block` consecutive elements of a row
+// (Section 4, Eq. 3; block == K is the row-wise scheme, smaller blocks the fine-grained
+// one of Section 3).  Scale (n, g) is stored at scales[g * N + n]: block-major, so that the
+// scales of neighbouring output channels are neighbours in memory.
+// |w| of finite fp16 orders like its 15 magnitude bits, so the maximum is taken on
+// integers.  The quotient is one IEEE fp32 division followed by one fp32->fp16 rounding;
+// a double rounding cannot occur because amax/28 is either exact in fp16 or at least
+// 2^-14 (relative) away from every fp16 midpoint.
+__global__ __launch_bounds__(256) void block_scale_kernel(const uint16_t* __restrict__ W, int64_t N, int64_t K,
+                                                           int64_t block, uint16_t* __restrict__ scales)
 {
-    const int64_t n = blockIdx.x;
-    const uint4* row = reinterpret_cast<const uint4*>(W + n * K);
-    const int64_t nvec = K / 8;
+    const int64_t G = K / block;
+    const int64_t n = blockIdx.x / G, g = blockIdx.x % G;
+    const uint4* row = reinterpret_cast<const uint4*>(W + n * K + g * block);
+    const int64_t nvec = block / 8;
     uint32_t amax = 0;
-    for (int64_t v = threadIdx.x; v < nvec; v += 256) {
+    for (int64_t v = threadIdx.x; v < nvec; v += blockDim.x) {
         uint4 d = row[v];
         uint32_t w[4] = {d.x, d.y, d.z, d.w};
 #pragma unroll
@@ -32,10 +37,10 @@ __global__ __launch_bounds__(256) void row_scale_kernel(const uint16_t* __restri
     if ((threadIdx.x & 63) == 0) s_max[threadIdx.x >> 6] = amax;
     __syncthreads();
     if (threadIdx.x == 0) {
-        amax = max(max(s_max[0], s_max[1]), max(s_max[2], s_max[3]));
+        for (unsigned w = 1; w < blockDim.x / 64; w++) amax = max(amax, s_max[w]);
         float a = (float)__builtin_bit_cast(_Float16, (uint16_t)amax);
         _Float16 S = (_Float16)(a / 28.0f);
-        scales[n] = __builtin_bit_cast(uint16_t, S);
+        scales[g * N + n] = __builtin_bit_cast(uint16_t, S);
     }
 }
 
@@ -70,7 +75,7 @@ __device__ __forceinline__ uint32_t e3m2_code(uint16_t wbits, float S)
 // One thread = one lane slot of one tile (64 weights): reads its eight 8-element runs of
 // W, quantizes them, and writes its 32 + 16 bytes of the two planes.
 __global__ __launch_bounds__(256) void quantize_pack_kernel(const uint16_t* __restrict__ W, int64_t N, int64_t K,
-                                                             const uint16_t* __restrict__ scales,
+                                                             int64_t block, const uint16_t* __restrict__ scales,
                                                              uint4* __restrict__ hi, uint4* __restrict__ lo)
 {
     const int64_t slot = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -86,7 +91,7 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(const uint16_t* __re
     for (int f = 0; f < 8; f++) {
         const int64_t n = nb * kTile + (f >> 1) * 16 + i;
         const int64_t k = kb * kTile + (f & 1) * 32 + g * 8;
-        const float S = (float)__builtin_bit_cast(_Float16, scales[n]);
+        const float S = (float)__builtin_bit_cast(_Float16, scales[(k / block) * N + n]);
         uint4 d = *reinterpret_cast<const uint4*>(W + n * K + k);
         uint32_t w2[4] = {d.x, d.y, d.z, d.w};
         uint32_t h = 0, l = 0;
@@ -150,7 +155,7 @@ __global__ __launch_bounds__(256) void unpack_codes_kernel(const u32x4* __restri
 // significand is exact, so the only rounding is the conversion to fp16.
 __global__ __launch_bounds__(256) void dequantize_kernel(const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
                                                           const uint16_t* __restrict__ scales, int64_t N, int64_t K,
-                                                          uint16_t* __restrict__ W_hat)
+                                                          int64_t block, uint16_t* __restrict__ W_hat)
 {
     const int64_t slot = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t tile = slot >> 6;
@@ -164,7 +169,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const u32x4* __restrict
     for (int f = 0; f < 8; f++) {
         const int64_t n = nb * kTile + (f >> 1) * 16 + i;
         const int64_t k = kb * kTile + (f & 1) * 32 + g * 8;
-        const float S = (float)__builtin_bit_cast(_Float16, scales[n]);
+        const float S = (float)__builtin_bit_cast(_Float16, scales[(k / block) * N + n]);
         const uint32_t H = tile_hi_dword(r, f), L = tile_lo_dword(r, f) >> (4 * (f & 1));
         uint32_t out[4];
 #pragma unroll
@@ -184,11 +189,12 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const u32x4* __restrict
 // ------------------------------------------------------------------ launchers
 static inline unsigned slot_blocks(int64_t N, int64_t K) { return (unsigned)(((N / kTile) * (K / kTile) * 64 + 255) / 256); }
 
-hipError_t launch_quantize_pack(const uint16_t* W, int64_t N, int64_t K, void* hi, void* lo, uint16_t* scales,
-                                hipStream_t stream)
+hipError_t launch_quantize_pack(const uint16_t* W, int64_t N, int64_t K, int64_t block, void* hi, void* lo,
+                                uint16_t* scales, hipStream_t stream)
 {
-    hipLaunchKernelGGL(row_scale_kernel, dim3((unsigned)N), dim3(256), 0, stream, W, K, scales);
-    hipLaunchKernelGGL(quantize_pack_kernel, dim3(slot_blocks(N, K)), dim3(256), 0, stream, W, N, K,
+    hipLaunchKernelGGL(block_scale_kernel, dim3((unsigned)(N * (K / block))), dim3(block >= 2048 ? 256 : 64), 0, stream,
+                       W, N, K, block, scales);
+    hipLaunchKernelGGL(quantize_pack_kernel, dim3(slot_blocks(N, K)), dim3(256), 0, stream, W, N, K, block,
                        (const uint16_t*)scales, (uint4*)hi, (uint4*)lo);
     return hipGetLastError();
 }
@@ -201,10 +207,10 @@ hipError_t launch_unpack_codes(const void* hi, const void* lo, int64_t N, int64_
 }
 
 hipError_t launch_dequantize(const void* hi, const void* lo, const uint16_t* scales, int64_t N, int64_t K,
-                             uint16_t* W_hat, hipStream_t stream)
+                             int64_t block, uint16_t* W_hat, hipStream_t stream)
 {
     hipLaunchKernelGGL(dequantize_kernel, dim3(slot_blocks(N, K)), dim3(256), 0, stream, (const u32x4*)hi,
-                       (const u32x4*)lo, scales, N, K, W_hat);
+                       (const u32x4*)lo, scales, N, K, block, W_hat);
     return hipGetLastError();
 }
 
