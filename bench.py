@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fp16-baseline", action="store_true")
     ap.add_argument("--legs", default="1,512", help="comma-separated M values to time")
+    ap.add_argument("--no-fused", action="store_true",
+                    help="skip the extra leg with q,k,v and gate,up concatenated along N (4 launches per layer)")
     ap.add_argument("--no-ablation", action="store_true",
                     help="skip the bias-shift ablation on the paper's kernel-table shapes")
     ap.add_argument("--copy-probe", action="store_true",
@@ -126,6 +128,43 @@ def main():
         res[M] = dict(ms_per_step=ms,
                       gbs=0.75 * weights_per_pass / (ms * 1e-3) / 1e9,
                       tflops=2.0 * M * weights_per_pass / (ms * 1e-3) / 1e12)
+
+    # ---- extra leg: projections that read the same input concatenated along N, as inference engines
+    # store them (q,k,v -> one [10240, 8192] weight; gate,up -> one [44032, 8192]).  Row scales are per
+    # output channel and tiles are ordered by channel block, so the concatenated planes and scales ARE the
+    # concatenation of the separate ones: same bytes, same results, 4 launches per layer instead of 7.
+    fused = None
+    if not args.no_fused:
+        names = [n for (n, _, _) in shapes]
+        groups = [[names.index(n) for n in g] for g in (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))]
+        fstack = []
+        for mats in stack:
+            fm = []
+            for g in groups:
+                Ks = {mats[i][1] for i in g}
+                assert len(Ks) == 1
+                fm.append((sum(mats[i][0] for i in g), Ks.pop(), torch.cat([mats[i][2] for i in g]),
+                           torch.cat([mats[i][3] for i in g]), torch.cat([mats[i][4] for i in g])))
+            fstack.append(fm)
+        fused = {"launches_per_step": sum(len(m) for m in fstack),
+                 "what": "q,k,v and gate,up concatenated along N (same planes, same scales, same results)"}
+        for M in legs:
+            xs = {K: inputs.activation(M, K, seed=inputs.workload_seed(WORKLOAD, 9000 + M + K), device=dev)
+                  for K in sorted({K for (_, _, K) in shapes})}
+            ys = {N: torch.empty((M, N), dtype=torch.float16, device=dev) for N in sorted({m[0] for m in fstack[0]})}
+            ws = P.new_workspace(max(max(P.fp6_linear_workspace_bytes(M, m[0], m[1]) for m in fstack[0]), 16), dev)
+
+            def fused_pass():
+                for fm in fstack:
+                    for (N, K, hi, lo, sc) in fm:
+                        P.fp6_linear(xs[K], hi, lo, sc, N, K, out=ys[N], workspace=ws)
+            ms = time_passes(fused_pass, args.steps, args.warmup)
+            fused["M%d" % M] = ({"ms_per_step": ms, "value": 0.75 * weights_per_pass / (ms * 1e-3) / 1e9, "unit": "GB/s",
+                                 "frac": 0.75 * weights_per_pass / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS} if M <= 118 else
+                                {"ms_per_step": ms, "value": 2.0 * M * weights_per_pass / (ms * 1e-3) / 1e12,
+                                 "unit": "TFLOP/s",
+                                 "frac": 2.0 * M * weights_per_pass / (ms * 1e-3) / 1e12 / MFMA_FP16_PEAK_TFLOPS})
+        del fstack
 
     # ---- fp16 dense GEMM on the same GPU, same stack (context, not the target)
     fp16 = None
@@ -277,6 +316,8 @@ def main():
                        "roofline": {"bound": "mfma", "achieved": r["tflops"], "peak": MFMA_FP16_PEAK_TFLOPS,
                                     "unit": "TFLOP/s", "frac": r["tflops"] / MFMA_FP16_PEAK_TFLOPS, "traffic": traffic.get(512),
                                     "kernel": "gemm_kernel (block_m 128), all %d launches of a step" % launches}}
+    if fused is not None:
+        out["fused_projections"] = fused
     if ablation is not None:
         out["bias_shift_ablation"] = ablation
     if fgq is not None:
