@@ -340,6 +340,134 @@ void fp6o_linear_fgq(const uint16_t *X, int64_t M, const uint8_t *codes, const u
     free(Xd);
 }
 
+/* ------------------------------------------------------------- FP5 E3M1, "4+1" */
+
+/*
+ * The five-bit format the paper names beside FP6 (Section 4: "similar setting is defined
+ * for FP5 E3M1"; Section 6: the 4+2 technique adapts to 5-bit quantization).  Eq. 2 with
+ * e = 3, bias 3 and ONE mantissa bit: code  s eee m  (0..31);
+ *   eee == 0 : subnormal, 2^(1-3) * (m/2) = m / 8          (0 and 0.125)
+ *   else     : normal,    2^(eee-3) * (1 + m/2)
+ * Largest magnitude 2^4 * 1.5 = 24, so the scale is S = RNE_fp16(max|w| / 24) (Eq. 3 with
+ * the format's own maximum).  Rounding, ties, saturation, signs and zero scales follow the
+ * same readings as the six-bit quantizer above.  The split is 4 + 1: sign and exponent, and
+ * the mantissa bit.  Bias shift (Eq. 5): bits s<<15 | eee<<10 | m<<9 are value * 2^-12.
+ */
+static int mag8_e3m1(int c4)     /* 8 * magnitude of the 4-bit magnitude code  eee m */
+{
+    int e = (c4 >> 1) & 7, m = c4 & 1;
+    if (e == 0) return m;
+    return (2 + m) << (e - 1);   /* 8 * 2^(e-3) * (2+m)/2 */
+}
+
+double fp5o_e3m1_value(int code)
+{
+    double v = (double)mag8_e3m1(code & 15) / 8.0;
+    return (code & 16) ? -v : v;
+}
+
+uint16_t fp5o_bias_shift_bits(int code)
+{
+    int s = (code >> 4) & 1, e = (code >> 1) & 7, m = code & 1;
+    return (uint16_t)((s << 15) | (e << 10) | (m << 9));
+}
+
+static int nearest_mag_code_e3m1(int64_t w_units, int64_t s_units)
+{
+    if (s_units == 0) return 0;
+    int best = 0;
+    int64_t best_d = -1;
+    for (int c = 0; c < 16; c++) {
+        /* | |w|/S - mag | * 8 * S  in units of 2^-24 */
+        int64_t d = 8 * w_units - s_units * (int64_t)mag8_e3m1(c);
+        if (d < 0) d = -d;
+        if (best_d < 0 || d < best_d || (d == best_d && (c & 1) == 0 && (best & 1) == 1)) {
+            best = c;
+            best_d = d;
+        }
+    }
+    return best;   /* |w|/S > 24 lands on c = 15: saturation */
+}
+
+/* W fp16 bits [N,K] -> codes [N,K] (0..31), scales fp16 bits [N] (row-wise) */
+int fp5o_quantize(const uint16_t *W, int64_t N, int64_t K, uint8_t *codes, uint16_t *scales)
+{
+    if (!W || !codes || !scales || N < 0 || K < 0) return FP6O_ERR_ARG;
+    int status = FP6O_OK;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; n++) {
+        const uint16_t *w = W + n * K;
+        int64_t amax = 0;
+        int bad = 0;
+        for (int64_t k = 0; k < K; k++) {
+            if (!half_is_finite(w[k])) bad = 1;
+            int64_t a = half_abs_units(w[k]);
+            if (a > amax) amax = a;
+        }
+        if (bad) {
+#pragma omp atomic write
+            status = FP6O_ERR_NONFINITE;
+            continue;
+        }
+        uint16_t S = round_units_to_half(amax, 24);
+        scales[n] = S;
+        int64_t s_units = half_abs_units(S);
+        for (int64_t k = 0; k < K; k++) {
+            int c4 = nearest_mag_code_e3m1(half_abs_units(w[k]), s_units);
+            codes[n * K + k] = (uint8_t)(((w[k] >> 15) << 4) | c4);
+        }
+    }
+    return status;
+}
+
+/* 4 + 1 split: first sub-number = sign and exponent, second = the mantissa bit */
+void fp5o_split41(const uint8_t *codes, int64_t count, uint8_t *hi4, uint8_t *lo1)
+{
+    for (int64_t i = 0; i < count; i++) {
+        hi4[i] = (uint8_t)((codes[i] >> 1) & 0xF);
+        lo1[i] = (uint8_t)(codes[i] & 0x1);
+    }
+}
+
+/* W_hat[n,k] = RNE_fp16( S_n * value(code) ) */
+void fp5o_dequantize(const uint8_t *codes, const uint16_t *scales, int64_t N, int64_t K, uint16_t *W_hat)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; n++) {
+        int64_t s_units = half_abs_units(scales[n]);
+        for (int64_t k = 0; k < K; k++) {
+            int c = codes[n * K + k];
+            uint16_t mag = round_units_to_half(s_units * (int64_t)mag8_e3m1(c & 15), 8);
+            W_hat[n * K + k] = (uint16_t)(((c >> 4) << 15) | mag);
+        }
+    }
+}
+
+/* Y[m,n] = S_n * sum_k X[m,k] * value(code[n,k]), double accumulation, scale after the sum */
+void fp5o_linear(const uint16_t *X, int64_t M, const uint8_t *codes, const uint16_t *scales,
+                 int64_t N, int64_t K, double *Y)
+{
+    double *Xd = (double *)malloc(sizeof(double) * (size_t)(M * K > 0 ? M * K : 1));
+    for (int64_t i = 0; i < M * K; i++) Xd[i] = fp6o_half_to_double(X[i]);
+#pragma omp parallel
+    {
+        double *wrow = (double *)malloc(sizeof(double) * (size_t)(K > 0 ? K : 1));
+#pragma omp for schedule(static)
+        for (int64_t n = 0; n < N; n++) {
+            for (int64_t k = 0; k < K; k++) wrow[k] = fp5o_e3m1_value(codes[n * K + k]);
+            double S = fp6o_half_to_double(scales[n]);
+            for (int64_t m = 0; m < M; m++) {
+                double acc = 0.0;
+                const double *x = Xd + m * K;
+                for (int64_t k = 0; k < K; k++) acc += x[k] * wrow[k];
+                Y[m * N + n] = S * acc;
+            }
+        }
+        free(wrow);
+    }
+    free(Xd);
+}
+
 /* number of host threads the loops above use */
 int fp6o_threads(void)
 {

@@ -46,6 +46,18 @@ def lib() -> ctypes.CDLL:
         L.fp6o_dequantize_fgq.argtypes = [p, p, i64, i64, i64, p]
         L.fp6o_linear_fgq.restype = None
         L.fp6o_linear_fgq.argtypes = [p, i64, p, p, i64, i64, i64, p]
+        L.fp5o_e3m1_value.restype = ctypes.c_double
+        L.fp5o_e3m1_value.argtypes = [ctypes.c_int]
+        L.fp5o_bias_shift_bits.restype = ctypes.c_uint16
+        L.fp5o_bias_shift_bits.argtypes = [ctypes.c_int]
+        L.fp5o_quantize.restype = ctypes.c_int
+        L.fp5o_quantize.argtypes = [p, i64, i64, p, p]
+        L.fp5o_split41.restype = None
+        L.fp5o_split41.argtypes = [p, i64, p, p]
+        L.fp5o_dequantize.restype = None
+        L.fp5o_dequantize.argtypes = [p, p, i64, i64, p]
+        L.fp5o_linear.restype = None
+        L.fp5o_linear.argtypes = [p, i64, p, p, i64, i64, p]
         L.fp6o_threads.restype = ctypes.c_int
         L.fp6o_threads.argtypes = []
         _LIB = L
@@ -187,4 +199,58 @@ def linear_fgq(X, codes, scales, block: int) -> np.ndarray:
     assert K == K2 and scales.shape == (N, K // block)
     Y = np.zeros((M, N), np.float64)
     lib().fp6o_linear_fgq(_ptr(X), M, _ptr(codes), _ptr(scales), N, K, block, _ptr(Y))
+    return Y
+
+
+# ---- FP5 E3M1, "4+1" (Section 4 last sentence; Section 6)
+
+def e3m1_value(code: int) -> float:
+    return float(lib().fp5o_e3m1_value(int(code)))
+
+
+def bias_shift_bits5(code: int) -> int:
+    return int(lib().fp5o_bias_shift_bits(int(code)))
+
+
+def quantize5(W):
+    """W fp16 [N,K] -> (codes uint8 [N,K] in 0..31, scales uint16 fp16-bits [N]); S = max|w| / 24."""
+    W = _bits(W)
+    if W.ndim != 2:
+        raise ValueError("W must be [N,K]")
+    N, K = W.shape
+    codes = np.zeros((N, K), np.uint8)
+    scales = np.zeros(N, np.uint16)
+    st = lib().fp5o_quantize(_ptr(W), N, K, _ptr(codes), _ptr(scales))
+    if st != 0:
+        raise ValueError("oracle: quantize5 failed (status %d)" % st)
+    return codes, scales
+
+
+def split41(codes):
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    hi4 = np.zeros_like(codes)
+    lo1 = np.zeros_like(codes)
+    lib().fp5o_split41(_ptr(codes), codes.size, _ptr(hi4), _ptr(lo1))
+    return hi4, lo1
+
+
+def dequantize5(codes, scales) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = _bits(scales).reshape(-1)
+    N, K = codes.shape
+    assert scales.size == N
+    out = np.zeros((N, K), np.uint16)
+    lib().fp5o_dequantize(_ptr(codes), _ptr(scales), N, K, _ptr(out))
+    return out
+
+
+def linear5(X, codes, scales) -> np.ndarray:
+    X = _bits(X)
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = _bits(scales).reshape(-1)
+    M, K = X.shape
+    N, K2 = codes.shape
+    assert K == K2 and scales.size == N
+    Y = np.zeros((M, N), np.float64)
+    lib().fp5o_linear(_ptr(X), M, _ptr(codes), _ptr(scales), N, K, _ptr(Y))
     return Y

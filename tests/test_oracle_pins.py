@@ -449,3 +449,93 @@ def test_fgq_linear_scale_multiplies_the_block_sum_not_the_rounded_weight():
     X = np.array([[1, 0, 0, 0, 1, 1, 1, 1]], np.float16)
     Y = O.linear_fgq(X, codes, S.view(np.uint16), 4)
     assert Y[0, 0] == float(S[0, 0]) * 7.0 + 0.5 * 4.0
+
+
+# ------------------------------------------------------------------ FP5 E3M1 ("4+1")
+
+GOLDEN5 = os.path.join(os.path.dirname(__file__), "golden", "e3m1_magnitudes.txt")
+MAGS5 = [float(l.split()[3]) for l in open(GOLDEN5) if l.strip() and not l.startswith("#")]
+
+
+def test_e3m1_values_closed_form_and_subset_of_e3m2():
+    assert len(MAGS5) == 16 and max(MAGS5) == 24.0 == 2.0 ** 4 * 1.5
+    for c in range(32):
+        s, E, m = c >> 4, (c >> 1) & 7, c & 1
+        x = Fraction(2) ** (E - 3) * (1 + Fraction(m, 2)) if E else Fraction(1, 4) * Fraction(m, 2)
+        assert Fraction(O.e3m1_value(c)) == (-x if s else x)
+        assert abs(O.e3m1_value(c)) == MAGS5[c & 15]
+        # same sign and exponent, mantissa bits "m0", in the six-bit format
+        assert O.e3m1_value(c) == O.e3m2_value(s << 5 | E << 2 | m << 1) or (c == 16 and O.e3m1_value(c) == 0.0)
+    assert np.signbit(O.e3m1_value(16))
+
+
+def test_e3m1_bias_shift_identity_numpy_fp16():
+    # Eq. 5 for the five-bit format: bits s<<15 | eee<<10 | m<<9 read as fp16, times 2^12, are the value
+    for c in range(32):
+        bits = O.bias_shift_bits5(c)
+        assert bits == ((c >> 4) << 15 | ((c >> 1) & 7) << 10 | (c & 1) << 9)
+        h = np.array([bits], np.uint16).view(np.float16).astype(np.float64)[0]
+        assert h * 4096.0 == O.e3m1_value(c)
+        if ((c >> 1) & 7) == 0 and (c & 1):
+            assert ((bits >> 10) & 31) == 0 and (bits & 0x3FF)        # an fp16 subnormal
+
+
+def test_e3m1_quantize_bruteforce_and_invariants():
+    rng = np.random.default_rng(51)
+    N, K = 6, 96
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+    W[0, :] = 0                                   # zero row
+    W[1, 5] = np.float16(-1e-7)                   # tiny negative keeps its sign
+    codes, scales = O.quantize5(W)
+    amax = np.abs(W.astype(np.float64)).max(axis=1)
+    assert np.array_equal(scales.view(np.float16), (amax / 24.0).astype(np.float16))
+    for n in range(N):
+        S = Fraction(float(scales[n:n + 1].view(np.float16)[0]))
+        for k in range(K):
+            w = Fraction(float(W[n, k]))
+            c = int(codes[n, k])
+            assert (c >> 4) == int(np.signbit(W[n, k]))
+            if S == 0:
+                assert (c & 15) == 0
+                continue
+            d = [abs(abs(w) / S - Fraction(MAGS5[i])) for i in range(16)]
+            best = min(d)
+            cands = [i for i in range(16) if d[i] == best]
+            want = cands[0] if len(cands) == 1 else [i for i in cands if i % 2 == 0][0]
+            assert (c & 15) == want
+    # the row maximum sits on the largest code
+    assert all((codes[n, np.abs(W[n].astype(np.float64)).argmax()] & 15) == 15 for n in range(1, N))
+    # idempotent on the grid: rows S0 * value(c) come back as c (including -0)
+    S0 = 2.0 ** -5
+    grid = np.array([[O.e3m1_value(c) * S0 for c in range(32)]], np.float16)
+    grid.view(np.uint16)[0, 16] = 0x8000
+    c2, s2 = O.quantize5(grid)
+    assert c2[0].tolist() == list(range(32)) and float(s2.view(np.float16)[0]) == S0
+    hi4, lo1 = O.split41(c2)
+    assert np.array_equal(hi4, c2 >> 1) and np.array_equal(lo1, c2 & 1)
+
+
+def test_e3m1_ties_go_to_even_code():
+    # S = 1/8 exactly (amax = 3): w = S * midpoint of two neighbouring magnitudes
+    mids = [(MAGS5[i] + MAGS5[i + 1]) / 2 for i in range(15)]
+    row = np.array([[3.0] + [m / 8.0 for m in mids]], np.float16)
+    assert all(float(v) * 8.0 == m for v, m in zip(row[0, 1:], mids))      # representable: real ties
+    codes, scales = O.quantize5(row)
+    assert float(scales.view(np.float16)[0]) == 0.125
+    for i, c in enumerate(codes[0, 1:]):
+        assert (c & 15) == (i if i % 2 == 0 else i + 1)
+
+
+def test_e3m1_dequantize_and_linear_vs_numpy():
+    rng = np.random.default_rng(52)
+    scales = rng.integers(1, 0x7000, 40).astype(np.uint16)
+    codes = np.tile(np.arange(32, dtype=np.uint8), (scales.size, 1))
+    vals = np.array([O.e3m1_value(c) for c in range(32)])
+    ref = (scales.view(np.float16).astype(np.float64)[:, None] * vals[None, :]).astype(np.float16)
+    assert np.array_equal(O.dequantize5(codes, scales), ref.view(np.uint16))
+    M, N, K = 4, 5, 64
+    X = rng.integers(-8, 9, (M, K)).astype(np.float16)
+    codes = rng.integers(0, 32, (N, K), dtype=np.uint8)
+    sc = np.array([2.0 ** -k for k in range(N)], np.float16)
+    Wv = vals[codes]
+    assert np.array_equal(O.linear5(X, codes, sc.view(np.uint16)), (X.astype(np.float64) @ Wv.T) * sc.astype(np.float64)[None, :])
