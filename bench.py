@@ -223,8 +223,8 @@ def main():
             r = [v[mode] / v["bias_shift"] for v in ablation["shapes"].values()]
             ablation["mean_slowdown_" + mode] = round(sum(r) / len(r), 3)
 
-    # ---- fine-grained scales (Section 3: FGQ, one scale per 128 elements of a row) against the
-    # row-wise scheme on the same six shapes, batch 8, cold weights
+    # ---- fine-grained scales (Section 3: FGQ, one scale per 128 elements of a row) and FP5 E3M1 "4+1"
+    # (Section 4, Section 6) against row-wise FP6 on the same six shapes, batch 8, cold weights
     fgq = None
     if not args.no_ablation:
         tcfg = inputs.WORKLOADS["paper_table_b1"]
@@ -236,25 +236,31 @@ def main():
             Y = torch.empty((M, N), dtype=torch.float16, device=dev)
             copies = max(2, min(64, int(1.0e9 / (0.75 * N * K))))
             row = {}
-            for mode in ("row_wise", "fgq"):
-                hi, lo, sc = P.fp6_quantize_pack(W) if mode == "row_wise" else P.fp6_quantize_pack_fgq(W, block)
+            for mode in ("row_wise", "fgq", "fp5"):
+                hi, lo, sc = (P.fp6_quantize_pack(W) if mode == "row_wise" else
+                              P.fp6_quantize_pack_fgq(W, block) if mode == "fgq" else P.fp5_quantize_pack(W))
                 pool = [(hi.clone(), lo.clone(), sc.clone()) for _ in range(copies)]
-                need = (P.fp6_linear_workspace_bytes(M, N, K) if mode == "row_wise"
-                        else P.fp6_linear_fgq_workspace_bytes(M, N, K, block))
+                need = (P.fp6_linear_workspace_bytes(M, N, K) if mode == "row_wise" else
+                        P.fp6_linear_fgq_workspace_bytes(M, N, K, block) if mode == "fgq" else
+                        P.fp5_linear_workspace_bytes(M, N, K))
                 ws = P.new_workspace(max(need, 16), dev)
 
                 def sweep():
                     for (h, l, s_) in pool:
                         if mode == "row_wise":
                             P.fp6_linear(X, h, l, s_, N, K, out=Y, workspace=ws)
-                        else:
+                        elif mode == "fgq":
                             P.fp6_linear_fgq(X, h, l, s_, N, K, block, out=Y, workspace=ws)
+                        else:
+                            P.fp5_linear(X, h, l, s_, N, K, out=Y, workspace=ws)
                 row[mode] = round(time_passes(sweep, 5, 2) * 1e3 / copies, 2)
                 del pool
             fgq["shapes"]["%s %dx%d" % (name, N, K)] = row
             del W
         r = [v["fgq"] / v["row_wise"] for v in fgq["shapes"].values()]
         fgq["mean_slowdown_fgq"] = round(sum(r) / len(r), 3)
+        r = [v["fp5"] / v["row_wise"] for v in fgq["shapes"].values()]
+        fgq["mean_time_ratio_fp5"] = round(sum(r) / len(r), 3)       # bytes ratio: 0.625 / 0.75 = 0.833
 
     # ---- CPU oracle on a bounded sample of the same workload (reported baseline)
     cpu = None
@@ -321,7 +327,7 @@ def main():
     if ablation is not None:
         out["bias_shift_ablation"] = ablation
     if fgq is not None:
-        out["fgq_vs_row_wise"] = fgq
+        out["fgq_and_fp5_vs_row_wise_fp6"] = fgq
     if fp16 is not None:
         out["fp16_dense_baseline"] = {"kind": "torch.matmul (hipBLASLt) on the dequantized fp16 weights, same stack",
                                       "ms_per_step": {m: v["ms_per_step"] for m, v in fp16.items()}}

@@ -205,6 +205,32 @@ int fp6_linear_fgq(const uint16_t *X, int64_t M, const void *hi_plane, const voi
                    const uint16_t *scales, int64_t N, int64_t K, int64_t block, uint16_t *Y,
                    void *workspace, size_t workspace_bytes, void *stream, int variant, int split_k);
 
+/*
+ * FP5 E3M1, "4+1" (Section 4: a similar setting is defined for FP5 E3M1; Section 6: the
+ * technique adapts to 5-bit quantization).  One sign bit, the same three exponent bits
+ * with bias 3, ONE mantissa bit; largest magnitude 24, so S_n = RNE_fp16(max|w| / 24); all
+ * other quantizer rules as for FP6.  A code is s<<4 | eee<<1 | m (0..31).  The 4-bit plane
+ * is exactly the FP6 one (N*K/2 bytes, same layout).  The second plane holds one mantissa
+ * bit per weight, N*K/8 bytes - 0.625 byte per weight in total: tile ti owns 512 contiguous
+ * bytes, lane l (as above) 8 of them; byte ti*512 + l*8 + (f/4)*4 + b holds, for the
+ * fragments f with the same f/4, the mantissa bits of elements b (grp 0) and 4+b (grp 1):
+ * bit 2*(f%4) = (f, grp0), bit 2*(f%4) + 1 = (f, grp1).  The bias shift (Eq. 5) pads the
+ * bit into position 9 of the fp16 pattern: value * 2^-12 again.
+ * Calls mirror the FP6 ones (row-wise scales); `variant` and `split_k` as in
+ * fp6_linear_variant, without the hints for waves, depth and dequantization.
+ */
+int fp5_packed_sizes(int64_t N, int64_t K, size_t *hi_bytes, size_t *lo_bytes, size_t *scale_bytes);
+int fp5_quantize_pack(const uint16_t *W, int64_t N, int64_t K, void *hi_plane, void *lo_plane,
+                      uint16_t *scales, void *stream);
+int fp5_unpack_codes(const void *hi_plane, const void *lo_plane, int64_t N, int64_t K,
+                     uint8_t *codes, void *stream);
+int fp5_dequantize(const void *hi_plane, const void *lo_plane, const uint16_t *scales,
+                   int64_t N, int64_t K, uint16_t *W_hat, void *stream);
+size_t fp5_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int variant, int split_k);
+int fp5_linear(const uint16_t *X, int64_t M, const void *hi_plane, const void *lo_plane,
+               const uint16_t *scales, int64_t N, int64_t K, uint16_t *Y,
+               void *workspace, size_t workspace_bytes, void *stream, int variant, int split_k);
+
 #ifdef __cplusplus
 }
 #endif

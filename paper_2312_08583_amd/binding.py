@@ -44,7 +44,8 @@ def FP6_HINT_DEQUANT(x: int) -> int:
 EXPORTS = ["fp6_layout_version", "fp6_status_string", "fp6_packed_sizes", "fp6_quantize_pack",
            "fp6_unpack_codes", "fp6_dequantize", "fp6_linear_workspace_bytes", "fp6_linear",
            "fp6_linear_variant_workspace_bytes", "fp6_linear_variant", "fp6_quantize_pack_fgq",
-           "fp6_dequantize_fgq", "fp6_linear_fgq_workspace_bytes", "fp6_linear_fgq"]
+           "fp6_dequantize_fgq", "fp6_linear_fgq_workspace_bytes", "fp6_linear_fgq", "fp5_packed_sizes",
+           "fp5_quantize_pack", "fp5_unpack_codes", "fp5_dequantize", "fp5_linear_workspace_bytes", "fp5_linear"]
 
 _LIB = None
 
@@ -91,6 +92,18 @@ def lib() -> ctypes.CDLL:
     L.fp6_linear_fgq_workspace_bytes.argtypes = [i64, i64, i64, i64, ci, ci]
     L.fp6_linear_fgq.restype = ci
     L.fp6_linear_fgq.argtypes = [p, i64, p, p, p, i64, i64, i64, p, p, sz, p, ci, ci]
+    L.fp5_packed_sizes.restype = ci
+    L.fp5_packed_sizes.argtypes = [i64, i64, ctypes.POINTER(sz), ctypes.POINTER(sz), ctypes.POINTER(sz)]
+    L.fp5_quantize_pack.restype = ci
+    L.fp5_quantize_pack.argtypes = [p, i64, i64, p, p, p, p]
+    L.fp5_unpack_codes.restype = ci
+    L.fp5_unpack_codes.argtypes = [p, p, i64, i64, p, p]
+    L.fp5_dequantize.restype = ci
+    L.fp5_dequantize.argtypes = [p, p, p, i64, i64, p, p]
+    L.fp5_linear_workspace_bytes.restype = sz
+    L.fp5_linear_workspace_bytes.argtypes = [i64, i64, i64, ci, ci]
+    L.fp5_linear.restype = ci
+    L.fp5_linear.argtypes = [p, i64, p, p, p, i64, i64, p, p, sz, p, ci, ci]
     _LIB = L
     return L
 
@@ -257,4 +270,63 @@ def fp6_linear_fgq(X: torch.Tensor, hi: torch.Tensor, lo: torch.Tensor, scales: 
     _check(lib().fp6_linear_fgq(xp, M, _dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"),
                                 _dev(scales, torch.float16, "scales"), N, K, block, _dev(out, torch.float16, "Y"),
                                 wp, wb, _stream(), variant, split_k), "fp6_linear_fgq")
+    return out
+
+
+# ---- FP5 E3M1 ("4+1")
+
+def fp5_packed_sizes(N: int, K: int) -> Tuple[int, int, int]:
+    a, b, c = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib().fp5_packed_sizes(N, K, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)), "fp5_packed_sizes")
+    return a.value, b.value, c.value
+
+
+def fp5_quantize_pack(W: torch.Tensor):
+    """W fp16 [N,K] -> (hi_plane uint8 [N*K/2], lo_plane uint8 [N*K/8], scales fp16 [N])."""
+    wp = _dev(W, torch.float16, "W")
+    N, K = W.shape
+    hb, lb, _ = fp5_packed_sizes(N, K)
+    hi = torch.empty(hb, dtype=torch.uint8, device=W.device)
+    lo = torch.empty(lb, dtype=torch.uint8, device=W.device)
+    scales = torch.empty(N, dtype=torch.float16, device=W.device)
+    _check(lib().fp5_quantize_pack(wp, N, K, hi.data_ptr(), lo.data_ptr(), scales.data_ptr(), _stream()),
+           "fp5_quantize_pack")
+    return hi, lo, scales
+
+
+def fp5_unpack_codes(hi: torch.Tensor, lo: torch.Tensor, N: int, K: int) -> torch.Tensor:
+    codes = torch.empty((N, K), dtype=torch.uint8, device=hi.device)
+    _check(lib().fp5_unpack_codes(_dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"), N, K,
+                                  codes.data_ptr(), _stream()), "fp5_unpack_codes")
+    return codes
+
+
+def fp5_dequantize(hi: torch.Tensor, lo: torch.Tensor, scales: torch.Tensor, N: int, K: int) -> torch.Tensor:
+    out = torch.empty((N, K), dtype=torch.float16, device=hi.device)
+    _check(lib().fp5_dequantize(_dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"),
+                                _dev(scales, torch.float16, "scales"), N, K, out.data_ptr(), _stream()),
+           "fp5_dequantize")
+    return out
+
+
+def fp5_linear_workspace_bytes(M: int, N: int, K: int, variant: int = FP6_VARIANT_AUTO, split_k: int = 0) -> int:
+    return int(lib().fp5_linear_workspace_bytes(M, N, K, variant, split_k))
+
+
+def fp5_linear(X: torch.Tensor, hi: torch.Tensor, lo: torch.Tensor, scales: torch.Tensor, N: int, K: int,
+               variant: int = FP6_VARIANT_AUTO, split_k: int = 0, out: Optional[torch.Tensor] = None,
+               workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    xp = _dev(X, torch.float16, "X")
+    M = X.shape[0]
+    if X.dim() != 2 or X.shape[1] != K:
+        raise Fp6Error("X must be [M,K]")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    if workspace is None:
+        workspace = new_workspace(fp5_linear_workspace_bytes(M, N, K, variant, split_k), X.device)
+    wp = workspace.data_ptr() if workspace is not None else None
+    wb = workspace.numel() if workspace is not None else 0
+    _check(lib().fp5_linear(xp, M, _dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"),
+                            _dev(scales, torch.float16, "scales"), N, K, _dev(out, torch.float16, "Y"),
+                            wp, wb, _stream(), variant, split_k), "fp5_linear")
     return out

@@ -38,7 +38,7 @@ static bool block_ok(int64_t K, int64_t block)
     return block >= FP6_TILE && block % FP6_TILE == 0 && ((block / FP6_TILE) & (block / FP6_TILE - 1)) == 0 && K % block == 0;
 }
 
-bool make_plan(int64_t M, int64_t N, int64_t K, int64_t block, int variant, int split_k, LinearPlan* plan)
+bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int variant, int split_k, LinearPlan* plan)
 {
     const int64_t ktiles = K / FP6_TILE, nblocks = N / FP6_TILE;
     // tuning hints ride in the upper bits of `variant`; 0 = automatic
@@ -53,6 +53,9 @@ bool make_plan(int64_t M, int64_t N, int64_t K, int64_t block, int variant, int 
     LinearPlan p{};
     p.variant = variant;
     p.dequant = hint_dequant;
+    p.format = format;
+    // the five-bit format exists for the default kernel configurations, row-wise scales only
+    if (format != kE3M2 && (block || hint_dequant || hint_waves || hint_depth)) return false;
     p.gshift = -1;
     if (block) {
         if (!block_ok(K, block) || hint_dequant || hint_waves || hint_depth) return false;
@@ -147,38 +150,38 @@ static size_t plan_workspace(const LinearPlan& p) { return p.split_k > 1 ? kZero
 using namespace fp6;
 
 // block == 0: one scale per row
-static int quantize_pack_any(const uint16_t* W, int64_t N, int64_t K, int64_t block, void* hi_plane, void* lo_plane,
+static int quantize_pack_any(int format, const uint16_t* W, int64_t N, int64_t K, int64_t block, void* hi_plane, void* lo_plane,
                              uint16_t* scales, void* stream)
 {
     if (!W || !hi_plane || !lo_plane || !scales) return FP6_ERR_NULL;
     if (!shape_ok(N, K) || (block && !block_ok(K, block))) return FP6_ERR_SHAPE;
     if (!aligned16(W) || !aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(scales)) return FP6_ERR_ALIGN;
-    return launch_quantize_pack(W, N, K, block ? block : K, hi_plane, lo_plane, scales, (hipStream_t)stream) ==
+    return launch_quantize_pack(format, W, N, K, block ? block : K, hi_plane, lo_plane, scales, (hipStream_t)stream) ==
                    hipSuccess
                ? FP6_OK
                : FP6_ERR_HIP;
 }
 
-static int dequantize_any(const void* hi_plane, const void* lo_plane, const uint16_t* scales, int64_t N, int64_t K,
+static int dequantize_any(int format, const void* hi_plane, const void* lo_plane, const uint16_t* scales, int64_t N, int64_t K,
                           int64_t block, uint16_t* W_hat, void* stream)
 {
     if (!hi_plane || !lo_plane || !scales || !W_hat) return FP6_ERR_NULL;
     if (!shape_ok(N, K) || (block && !block_ok(K, block))) return FP6_ERR_SHAPE;
     if (!aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(scales) || !aligned16(W_hat)) return FP6_ERR_ALIGN;
-    return launch_dequantize(hi_plane, lo_plane, scales, N, K, block ? block : K, W_hat, (hipStream_t)stream) ==
+    return launch_dequantize(format, hi_plane, lo_plane, scales, N, K, block ? block : K, W_hat, (hipStream_t)stream) ==
                    hipSuccess
                ? FP6_OK
                : FP6_ERR_HIP;
 }
 
-static size_t workspace_any(int64_t M, int64_t N, int64_t K, int64_t block, int variant, int split_k)
+static size_t workspace_any(int format, int64_t M, int64_t N, int64_t K, int64_t block, int variant, int split_k)
 {
     LinearPlan p;
-    if (M <= 0 || M > (int64_t)1 << 24 || !shape_ok(N, K) || !make_plan(M, N, K, block, variant, split_k, &p)) return 0;
+    if (M <= 0 || M > (int64_t)1 << 24 || !shape_ok(N, K) || !make_plan(format, M, N, K, block, variant, split_k, &p)) return 0;
     return plan_workspace(p);
 }
 
-static int linear_any(const uint16_t* X, int64_t M, const void* hi_plane, const void* lo_plane,
+static int linear_any(int format, const uint16_t* X, int64_t M, const void* hi_plane, const void* lo_plane,
                       const uint16_t* scales, int64_t N, int64_t K, int64_t block, uint16_t* Y, void* workspace,
                       size_t workspace_bytes, void* stream, int variant, int split_k)
 {
@@ -188,7 +191,7 @@ static int linear_any(const uint16_t* X, int64_t M, const void* hi_plane, const 
         !aligned16(workspace))
         return FP6_ERR_ALIGN;
     LinearPlan p;
-    if (!make_plan(M, N, K, block, variant, split_k, &p)) return FP6_ERR_VARIANT;
+    if (!make_plan(format, M, N, K, block, variant, split_k, &p)) return FP6_ERR_VARIANT;
     const size_t need = plan_workspace(p);
     if (need > 0 && (!workspace || workspace_bytes < need)) return FP6_ERR_WORKSPACE;
     hipError_t e = (p.variant == FP6_VARIANT_DECODE)
@@ -227,14 +230,14 @@ int fp6_packed_sizes(int64_t N, int64_t K, size_t* hi_bytes, size_t* lo_bytes, s
 int fp6_quantize_pack(const uint16_t* W, int64_t N, int64_t K, void* hi_plane, void* lo_plane, uint16_t* scales,
                       void* stream)
 {
-    return quantize_pack_any(W, N, K, 0, hi_plane, lo_plane, scales, stream);
+    return quantize_pack_any(kE3M2, W, N, K, 0, hi_plane, lo_plane, scales, stream);
 }
 
 int fp6_quantize_pack_fgq(const uint16_t* W, int64_t N, int64_t K, int64_t block, void* hi_plane, void* lo_plane,
                           uint16_t* scales, void* stream)
 {
     if (block <= 0) return FP6_ERR_SHAPE;
-    return quantize_pack_any(W, N, K, block, hi_plane, lo_plane, scales, stream);
+    return quantize_pack_any(kE3M2, W, N, K, block, hi_plane, lo_plane, scales, stream);
 }
 
 int fp6_unpack_codes(const void* hi_plane, const void* lo_plane, int64_t N, int64_t K, uint8_t* codes, void* stream)
@@ -242,50 +245,51 @@ int fp6_unpack_codes(const void* hi_plane, const void* lo_plane, int64_t N, int6
     if (!hi_plane || !lo_plane || !codes) return FP6_ERR_NULL;
     if (!shape_ok(N, K)) return FP6_ERR_SHAPE;
     if (!aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(codes)) return FP6_ERR_ALIGN;
-    return launch_unpack_codes(hi_plane, lo_plane, N, K, codes, (hipStream_t)stream) == hipSuccess ? FP6_OK
-                                                                                                    : FP6_ERR_HIP;
+    return launch_unpack_codes(kE3M2, hi_plane, lo_plane, N, K, codes, (hipStream_t)stream) == hipSuccess
+               ? FP6_OK
+               : FP6_ERR_HIP;
 }
 
 int fp6_dequantize(const void* hi_plane, const void* lo_plane, const uint16_t* scales, int64_t N, int64_t K,
                    uint16_t* W_hat, void* stream)
 {
-    return dequantize_any(hi_plane, lo_plane, scales, N, K, 0, W_hat, stream);
+    return dequantize_any(kE3M2, hi_plane, lo_plane, scales, N, K, 0, W_hat, stream);
 }
 
 int fp6_dequantize_fgq(const void* hi_plane, const void* lo_plane, const uint16_t* scales, int64_t N, int64_t K,
                        int64_t block, uint16_t* W_hat, void* stream)
 {
     if (block <= 0) return FP6_ERR_SHAPE;
-    return dequantize_any(hi_plane, lo_plane, scales, N, K, block, W_hat, stream);
+    return dequantize_any(kE3M2, hi_plane, lo_plane, scales, N, K, block, W_hat, stream);
 }
 
 size_t fp6_linear_variant_workspace_bytes(int64_t M, int64_t N, int64_t K, int variant, int split_k)
 {
-    return workspace_any(M, N, K, 0, variant, split_k);
+    return workspace_any(kE3M2, M, N, K, 0, variant, split_k);
 }
 
 size_t fp6_linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
-    return workspace_any(M, N, K, 0, FP6_VARIANT_AUTO, 0);
+    return workspace_any(kE3M2, M, N, K, 0, FP6_VARIANT_AUTO, 0);
 }
 
 size_t fp6_linear_fgq_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t block, int variant, int split_k)
 {
-    return block > 0 ? workspace_any(M, N, K, block, variant, split_k) : 0;
+    return block > 0 ? workspace_any(kE3M2, M, N, K, block, variant, split_k) : 0;
 }
 
 int fp6_linear_variant(const uint16_t* X, int64_t M, const void* hi_plane, const void* lo_plane,
                        const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                        size_t workspace_bytes, void* stream, int variant, int split_k)
 {
-    return linear_any(X, M, hi_plane, lo_plane, scales, N, K, 0, Y, workspace, workspace_bytes, stream, variant,
+    return linear_any(kE3M2, X, M, hi_plane, lo_plane, scales, N, K, 0, Y, workspace, workspace_bytes, stream, variant,
                       split_k);
 }
 
 int fp6_linear(const uint16_t* X, int64_t M, const void* hi_plane, const void* lo_plane, const uint16_t* scales,
                int64_t N, int64_t K, uint16_t* Y, void* workspace, size_t workspace_bytes, void* stream)
 {
-    return linear_any(X, M, hi_plane, lo_plane, scales, N, K, 0, Y, workspace, workspace_bytes, stream,
+    return linear_any(kE3M2, X, M, hi_plane, lo_plane, scales, N, K, 0, Y, workspace, workspace_bytes, stream,
                       FP6_VARIANT_AUTO, 0);
 }
 
@@ -294,7 +298,53 @@ int fp6_linear_fgq(const uint16_t* X, int64_t M, const void* hi_plane, const voi
                    void* stream, int variant, int split_k)
 {
     if (block <= 0) return FP6_ERR_SHAPE;
-    return linear_any(X, M, hi_plane, lo_plane, scales, N, K, block, Y, workspace, workspace_bytes, stream, variant,
+    return linear_any(kE3M2, X, M, hi_plane, lo_plane, scales, N, K, block, Y, workspace, workspace_bytes, stream, variant,
+                      split_k);
+}
+
+// ---- FP5 E3M1, "4+1"
+
+int fp5_packed_sizes(int64_t N, int64_t K, size_t* hi_bytes, size_t* lo_bytes, size_t* scale_bytes)
+{
+    if (!shape_ok(N, K)) return FP6_ERR_SHAPE;
+    if (hi_bytes) *hi_bytes = (size_t)(N * K / 2);
+    if (lo_bytes) *lo_bytes = (size_t)(N * K / 8);
+    if (scale_bytes) *scale_bytes = (size_t)(2 * N);
+    return FP6_OK;
+}
+
+int fp5_quantize_pack(const uint16_t* W, int64_t N, int64_t K, void* hi_plane, void* lo_plane, uint16_t* scales,
+                      void* stream)
+{
+    return quantize_pack_any(kE3M1, W, N, K, 0, hi_plane, lo_plane, scales, stream);
+}
+
+int fp5_unpack_codes(const void* hi_plane, const void* lo_plane, int64_t N, int64_t K, uint8_t* codes, void* stream)
+{
+    if (!hi_plane || !lo_plane || !codes) return FP6_ERR_NULL;
+    if (!shape_ok(N, K)) return FP6_ERR_SHAPE;
+    if (!aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(codes)) return FP6_ERR_ALIGN;
+    return launch_unpack_codes(kE3M1, hi_plane, lo_plane, N, K, codes, (hipStream_t)stream) == hipSuccess
+               ? FP6_OK
+               : FP6_ERR_HIP;
+}
+
+int fp5_dequantize(const void* hi_plane, const void* lo_plane, const uint16_t* scales, int64_t N, int64_t K,
+                   uint16_t* W_hat, void* stream)
+{
+    return dequantize_any(kE3M1, hi_plane, lo_plane, scales, N, K, 0, W_hat, stream);
+}
+
+size_t fp5_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int variant, int split_k)
+{
+    return workspace_any(kE3M1, M, N, K, 0, variant, split_k);
+}
+
+int fp5_linear(const uint16_t* X, int64_t M, const void* hi_plane, const void* lo_plane, const uint16_t* scales,
+               int64_t N, int64_t K, uint16_t* Y, void* workspace, size_t workspace_bytes, void* stream, int variant,
+               int split_k)
+{
+    return linear_any(kE3M1, X, M, hi_plane, lo_plane, scales, N, K, 0, Y, workspace, workspace_bytes, stream, variant,
                       split_k);
 }
 

@@ -6,6 +6,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "fp6_internal.hpp"
+
 namespace fp6 {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
@@ -13,12 +15,16 @@ typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kTile = 64;             // tile edge in n and in k
 constexpr int kHiTileBytes = 2048;    // 4-bit plane bytes per tile
 constexpr int kLoTileBytes = 1024;    // 2-bit plane bytes per tile
 constexpr int kHiTileVec = kHiTileBytes / 16;   // uint4 per tile
 constexpr int kLoTileVec = kLoTileBytes / 16;
+constexpr int kLo1TileBytes = 512;    // 1-bit plane bytes per tile (FP5): 8 bytes per lane
+template <int FMT>
+constexpr int kLoBytesOf = FMT == kE3M2 ? kLoTileBytes : kLo1TileBytes;
 
 // bitwise select: mask bit 1 -> a, mask bit 0 -> b   (one v_bitop3_b32)
 __device__ __forceinline__ uint32_t bit_select(uint32_t a, uint32_t b, uint32_t mask)
@@ -30,11 +36,13 @@ __device__ __forceinline__ uint32_t bit_select(uint32_t a, uint32_t b, uint32_t 
 struct TileRaw {
     u32x4 hi0;   // fragments 0..3: one dword per fragment (8 sign+exponent sub-numbers)
     u32x4 hi1;   // fragments 4..7
-    u32x4 lo;    // dword d: the mantissa sub-numbers of fragments 2d and 2d+1
+    u32x4 lo;    // FP6: dword d = the mantissa sub-numbers of fragments 2d and 2d+1
+                 // FP5: dwords 0, 1 only; dword d = the mantissa bits of fragments 4d .. 4d+3
 };
 
 // Three coalesced 128-bit loads per lane.  The weight stream is read exactly once, so
 // it is marked non-temporal to keep it from evicting X and the partial sums.
+template <int FMT = kE3M2>
 __device__ __forceinline__ TileRaw load_tile(const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
                                              size_t tile_index, int lane)
 {
@@ -42,7 +50,12 @@ __device__ __forceinline__ TileRaw load_tile(const u32x4* __restrict__ hi, const
     const u32x4* h = hi + tile_index * kHiTileVec + lane;
     r.hi0 = __builtin_nontemporal_load(h);
     r.hi1 = __builtin_nontemporal_load(h + 64);
-    r.lo = __builtin_nontemporal_load(lo + tile_index * kLoTileVec + lane);
+    if (FMT == kE3M2) {
+        r.lo = __builtin_nontemporal_load(lo + tile_index * kLoTileVec + lane);
+    } else {
+        const u32x2 l = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(lo) + tile_index * 64 + lane);
+        r.lo = u32x4{l.x, l.y, 0u, 0u};
+    }
     return r;
 }
 
@@ -112,9 +125,28 @@ __device__ __forceinline__ half8 unpack_fragment(uint32_t H, uint32_t L)
     return h;
 }
 
-template <int DQ = kBiasShift>
+// FP5 (E3M1): the same padding with one mantissa bit, which lands on bit 1 of the byte
+// s00eeem0; bit 0 is cleared by the final mask.  M = the dword of the 1-bit plane that covers
+// fragments 4*(f/4) .. +3: byte b holds, for fragment f, mant(grp0) at bit 2*(f%4) and
+// mant(grp1) at bit 2*(f%4) + 1.
+__device__ __forceinline__ half8 unpack_fragment_e3m1(uint32_t H, uint32_t M, int fq)
+{
+    const uint32_t L0 = fq ? M >> (2 * fq - 1) : M << 1;    // grp0 bit -> bit 1
+    const uint32_t L1 = M >> (2 * fq);                      // grp1 bit -> bit 1
+    uint32_t u0 = bit_select(H << 7, bit_select(H, L0, 0x1C1C1C1Cu), 0x80808080u);
+    uint32_t u1 = bit_select(H << 6, bit_select(H >> 3, L1, 0x1C1C1C1Cu), 0x80808080u);
+    u32x4 w;
+    w.x = (u0 << 8) & 0x9E009E00u;
+    w.y = u0 & 0x9E009E00u;
+    w.z = (u1 << 8) & 0x9E009E00u;
+    w.w = u1 & 0x9E009E00u;
+    return __builtin_bit_cast(half8, w);
+}
+
+template <int DQ = kBiasShift, int FMT = kE3M2>
 __device__ __forceinline__ half8 unpack_tile_fragment(const TileRaw& r, int f)
 {
+    if (FMT == kE3M1) return unpack_fragment_e3m1(tile_hi_dword(r, f), r.lo[f >> 2], f & 3);
     return unpack_fragment<DQ>(tile_hi_dword(r, f), tile_lo_dword(r, f) >> (4 * (f & 1)));
 }
 

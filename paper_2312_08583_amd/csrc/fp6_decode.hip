@@ -33,12 +33,12 @@ __device__ __forceinline__ XFrag load_x(const uint16_t* __restrict__ xrow, int k
     return x;
 }
 
-template <int DQ>
+template <int DQ, int FMT>
 __device__ __forceinline__ void tile_mac(const TileRaw& r, const XFrag& x, float4v acc[4])
 {
 #pragma unroll
     for (int f = 0; f < 8; f++) {
-        half8 w = unpack_tile_fragment<DQ>(r, f);
+        half8 w = unpack_tile_fragment<DQ, FMT>(r, f);
         acc[f >> 1] = mfma16x16x32(w, (f & 1) ? x.q1 : x.q0, acc[f >> 1]);
     }
 }
@@ -51,7 +51,7 @@ __device__ __forceinline__ void tile_mac(const TileRaw& r, const XFrag& x, float
 // to the running sum - "after matrix multiplication, before the accumulation" (Section 5.2).
 // The scales of the workgroup's 64 channels for its whole K-slice (128 bytes per block) are
 // copied to LDS first, while the first tiles are already on their way.
-template <int WAVES, int D, int DQ, bool FGQ>
+template <int WAVES, int D, int DQ, bool FGQ, int FMT>
 __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
     const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
                 float4v part[4];
 #pragma unroll
                 for (int t = 0; t < 4; t++) part[t] = float4v{0.f, 0.f, 0.f, 0.f};
-                tile_mac<DQ>(raw[slot], xf[slot], part);
+                tile_mac<DQ, FMT>(raw[slot], xf[slot], part);
                 const uint16_t* sg = gscale + ((k >> gshift) - group0) * kTile + g * 4;
 #pragma unroll
                 for (int t = 0; t < 4; t++) {
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
                     for (int r = 0; r < 4; r++) acc[t][r] += part[t][r] * (float)sv[r];
                 }
             } else {
-                tile_mac<DQ>(raw[slot], xf[slot], acc);
+                tile_mac<DQ, FMT>(raw[slot], xf[slot], acc);
             }
         };
 
@@ -126,7 +126,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
 #pragma unroll
         for (int u = 0; u < D - 1; u++) {
             const int k = kt0 + min(u, cnt - 1) * WAVES;
-            raw[u] = load_tile(hi, lo, tile0 + k, lane);
+            raw[u] = load_tile<FMT>(hi, lo, tile0 + k, lane);
             xf[u] = load_x(xrow, k);
         }
         // steady state, branch-free: D tiles per trip, each step refills the slot freed one step ago
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
 #pragma unroll
             for (int u = 0; u < D; u++) {
                 const int k = kt0 + (j0 + u + D - 1) * WAVES;
-                raw[(u + D - 1) % D] = load_tile(hi, lo, tile0 + k, lane);
+                raw[(u + D - 1) % D] = load_tile<FMT>(hi, lo, tile0 + k, lane);
                 xf[(u + D - 1) % D] = load_x(xrow, k);
                 mac(u, kt0 + (j0 + u) * WAVES);
             }
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
             if (j < cnt) {
                 if (j + D - 1 < cnt) {
                     const int k = kt0 + (j + D - 1) * WAVES;
-                    raw[(v + D - 1) % D] = load_tile(hi, lo, tile0 + k, lane);
+                    raw[(v + D - 1) % D] = load_tile<FMT>(hi, lo, tile0 + k, lane);
                     xf[(v + D - 1) % D] = load_x(xrow, k);
                 }
                 mac(v % D, kt0 + j * WAVES);
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     }
 }
 
-template <int WAVES, int D, int DQ = kBiasShift, bool FGQ = false>
+template <int WAVES, int D, int DQ = kBiasShift, bool FGQ = false, int FMT = kE3M2>
 static hipError_t launch_decode_t(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
                                   const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                                   hipStream_t stream)
@@ -233,7 +233,7 @@ static hipError_t launch_decode_t(const LinearPlan& p, const uint16_t* X, int64_
     const unsigned grid = (unsigned)((N / kTile) * p.split_k);
     // FGQ: 128 bytes of scales per block of K in a workgroup's slice (a slice may start inside a block)
     const size_t lds = FGQ ? (size_t)(((K / kTile / p.split_k - 1) >> p.gshift) + 2) * 128 : 0;
-    hipLaunchKernelGGL((decode_kernel<WAVES, D, DQ, FGQ>), dim3(grid), dim3(WAVES * 64), lds, stream, X, (int)M,
+    hipLaunchKernelGGL((decode_kernel<WAVES, D, DQ, FGQ, FMT>), dim3(grid), dim3(WAVES * 64), lds, stream, X, (int)M,
                        (const u32x4*)hi, (const u32x4*)lo, scales, (int)N, (int)K, Y, partials, counters, slots,
                        p.split_k, p.pairwise, p.gshift);
     return hipGetLastError();
@@ -243,6 +243,7 @@ hipError_t launch_decode(const LinearPlan& p, const uint16_t* X, int64_t M, cons
                          const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                          hipStream_t stream)
 {
+    if (p.format == kE3M1) return launch_decode_t<4, 4, kBiasShift, false, kE3M1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     if (p.gshift >= 0) return launch_decode_t<4, 4, kBiasShift, true>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     if (p.dequant == kIntRebias) return launch_decode_t<4, 4, kIntRebias>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     if (p.dequant == kHalfMul) return launch_decode_t<4, 4, kHalfMul>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);

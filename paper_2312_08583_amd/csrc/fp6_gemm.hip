@@ -73,7 +73,7 @@ __device__ __forceinline__ void wait_vmcnt()
 // the end of the block they are multiplied by the block's scales and added to the running
 // sum - "after matrix multiplication, before the accumulation" (Section 5.2).  The scales of
 // a wavefront's 64 channels (128 bytes per block) ride along with every stage of the DMA ring.
-template <int BM, int D, int WN, int DQ, bool FGQ>
+template <int BM, int D, int WN, int DQ, bool FGQ, int FMT>
 __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
     const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
     const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
@@ -153,10 +153,12 @@ __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
 #pragma unroll
         for (int c = 0; c < WN; c++) {
             const unsigned char* hb = reinterpret_cast<const unsigned char*>(hi) + (tile0[c] + kt) * kHiTileBytes;
-            const unsigned char* lb = reinterpret_cast<const unsigned char*>(lo) + (tile0[c] + kt) * kLoTileBytes;
+            const unsigned char* lb = reinterpret_cast<const unsigned char*>(lo) + (tile0[c] + kt) * kLoBytesOf<FMT>;
             dma16(hb, wlane, sb + wlds + c * kWaveTileBytes);
             dma16(hb + 1024, wlane, sb + wlds + c * kWaveTileBytes + 1024);
-            dma16(lb, wlane, sb + wlds + c * kWaveTileBytes + 2048);
+            // FP5: the 1-bit plane has 512 bytes per tile; the upper lanes fetch them a second time
+            // (into the unused half of the stage's 1 KB) rather than bytes of the next tile
+            dma16(lb, FMT == kE3M2 ? wlane : (wlane & 511u), sb + wlds + c * kWaveTileBytes + 2048);
         }
         if (FGQ) {
             // scales of this tile's block for the wavefront's 64 channels: 128 bytes, fetched by lanes
@@ -198,7 +200,12 @@ __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
         for (int c = 0; c < WN; c++) {
             raw[c].hi0 = *reinterpret_cast<const u32x4*>(wt + c * kWaveTileBytes + wlane);
             raw[c].hi1 = *reinterpret_cast<const u32x4*>(wt + c * kWaveTileBytes + 1024 + wlane);
-            raw[c].lo = *reinterpret_cast<const u32x4*>(wt + c * kWaveTileBytes + 2048 + wlane);
+            if (FMT == kE3M2) {
+                raw[c].lo = *reinterpret_cast<const u32x4*>(wt + c * kWaveTileBytes + 2048 + wlane);
+            } else {
+                const u32x2 l = *reinterpret_cast<const u32x2*>(wt + c * kWaveTileBytes + 2048 + lane * 8);
+                raw[c].lo = u32x4{l.x, l.y, 0u, 0u};
+            }
         }
 #pragma unroll
         for (int q = 0; q < 2; q++) {
@@ -209,7 +216,7 @@ __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
             }
 #pragma unroll
             for (int t = 0; t < NT; t++) {
-                half8 w = unpack_tile_fragment<DQ>(raw[t / 4], 2 * (t % 4) + q);
+                half8 w = unpack_tile_fragment<DQ, FMT>(raw[t / 4], 2 * (t % 4) + q);
 #pragma unroll
                 for (int a = 0; a < MT; a++) {
                     if (FGQ) part[a][t] = mfma16x16x32(w, xf[a], part[a][t]);
@@ -238,7 +245,9 @@ __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
         // shadow), and the LDS operand reads of the second k block are spread over the MFMAs of
         // the first.
 #if FP6_GEMM_HINTS
-        if (!FGQ) {
+        // (tuned for the instruction mix of the FP6 bias-shift unpack; the other variants are left to the compiler,
+        // whose schedule needs fewer registers)
+        if (!FGQ && FMT == kE3M2 && DQ != kHalfMul) {
         __builtin_amdgcn_sched_group_barrier(0x100, 3 * WN + MT, 0);     // planes + operands of k block 0
         __builtin_amdgcn_sched_group_barrier(0x002, 15, 0);              // first fragment
 #pragma unroll
@@ -336,7 +345,7 @@ __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
     }
 }
 
-template <int BM, int D, int WN, int DQ = kBiasShift, bool FGQ = false>
+template <int BM, int D, int WN, int DQ = kBiasShift, bool FGQ = false, int FMT = kE3M2>
 static hipError_t launch_gemm_t(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
                                 const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                                 hipStream_t stream)
@@ -346,7 +355,7 @@ static hipError_t launch_gemm_t(const LinearPlan& p, const uint16_t* X, int64_t 
     const int64_t mblk = (M + BM - 1) / BM, nblk = (N / kTile + kGemmBlocksN - 1) / kGemmBlocksN;
     const unsigned grid = (unsigned)(nblk >= 8 ? mblk * ((nblk + 7) / 8 * 8) * p.split_k
                                                : mblk * ((nblk * p.split_k + 7) / 8 * 8));   // padded: see the id mapping
-    hipLaunchKernelGGL((gemm_kernel<BM, D, WN, DQ, FGQ>), dim3(grid), dim3(kGemmBlocksN / WN * 64), 0, stream, X, (int)M,
+    hipLaunchKernelGGL((gemm_kernel<BM, D, WN, DQ, FGQ, FMT>), dim3(grid), dim3(kGemmBlocksN / WN * 64), 0, stream, X, (int)M,
                        (const u32x4*)hi, (const u32x4*)lo, scales, (int)N, (int)K, Y, partials, counters, p.split_k, p.gshift);
     return hipGetLastError();
 }
@@ -355,6 +364,11 @@ hipError_t launch_gemm(const LinearPlan& p, const uint16_t* X, int64_t M, const 
                        const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                        hipStream_t stream)
 {
+    if (p.format == kE3M1) {
+        if (p.block_m == 32) return launch_gemm_t<32, 4, 1, kBiasShift, false, kE3M1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        if (p.block_m == 64) return launch_gemm_t<64, 4, 1, kBiasShift, false, kE3M1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        return launch_gemm_t<128, 3, 1, kBiasShift, false, kE3M1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+    }
     if (p.gshift >= 0) {
         if (p.block_m == 32) return launch_gemm_t<32, 4, 1, kBiasShift, true>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
         return launch_gemm_t<64, 4, 1, kBiasShift, true>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);

@@ -7,6 +7,10 @@
 
 namespace fp6 {
 
+// Weight formats.  kE3M2: FP6, planes of 4 + 2 bits (Section 5.1).  kE3M1: FP5, the same
+// sign/exponent plane plus a 1-bit mantissa plane ("4+1"; Section 4, Section 6).
+enum Format { kE3M2 = 6, kE3M1 = 5 };
+
 // Workspace layout: [arrival counters: kCounterBytes][meeting slots: kSlotBytes][fp32 partial sums].
 // The first two regions (kZeroBytes) are zero whenever no call is running.
 constexpr int kCounterStride = 16;      // uint32 words between two counters: one 64-byte line each, so that
@@ -16,12 +20,12 @@ constexpr size_t kCounterBytes = (size_t)kMaxCounters * kCounterStride * sizeof(
 constexpr size_t kSlotBytes = (size_t)4 << 20;
 constexpr size_t kZeroBytes = kCounterBytes + kSlotBytes;
 
-// `block` = elements along K that share a scale (K itself for the row-wise scheme); scale (n, g) at scales[g*N + n]
-hipError_t launch_quantize_pack(const uint16_t* W, int64_t N, int64_t K, int64_t block, void* hi, void* lo,
+// `format` = 6 (E3M2) or 5 (E3M1).  `block` = elements along K that share a scale (K itself for the row-wise scheme); scale (n, g) at scales[g*N + n]
+hipError_t launch_quantize_pack(int format, const uint16_t* W, int64_t N, int64_t K, int64_t block, void* hi, void* lo,
                                 uint16_t* scales, hipStream_t stream);
-hipError_t launch_unpack_codes(const void* hi, const void* lo, int64_t N, int64_t K, uint8_t* codes,
+hipError_t launch_unpack_codes(int format, const void* hi, const void* lo, int64_t N, int64_t K, uint8_t* codes,
                                hipStream_t stream);
-hipError_t launch_dequantize(const void* hi, const void* lo, const uint16_t* scales, int64_t N, int64_t K,
+hipError_t launch_dequantize(int format, const void* hi, const void* lo, const uint16_t* scales, int64_t N, int64_t K,
                              int64_t block, uint16_t* W_hat, hipStream_t stream);
 
 // A fully resolved launch plan for fp6_linear.
@@ -33,6 +37,7 @@ struct LinearPlan {
     int depth;          // tiles in the per-wavefront prefetch ring
     size_t partial_bytes;   // fp32 partial sums needed in the workspace (0 if split_k == 1)
     int counters;       // arrival counters used (0 if split_k == 1)
+    int format;         // 6: FP6 E3M2 (4+2 planes); 5: FP5 E3M1 (4+1 planes)
     int gshift;         // fine-grained scales: log2(block / 64); -1 = one scale per row
     int dequant;        // 0: bias-shift unpack (the method); 1, 2: ablations (integer re-bias, fp16 multiply)
     int pairwise;       // DECODE with split_k > 1: K-slices meet pairwise in the slot region (1) or at a counter (0)
@@ -40,7 +45,7 @@ struct LinearPlan {
 
 // Heuristic (or caller-forced) plan; returns false if the request is invalid for the shape.
 // `block` = elements along K per scale (0 = row-wise).
-bool make_plan(int64_t M, int64_t N, int64_t K, int64_t block, int variant, int split_k, LinearPlan* plan);
+bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int variant, int split_k, LinearPlan* plan);
 
 hipError_t launch_decode(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
                          const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,

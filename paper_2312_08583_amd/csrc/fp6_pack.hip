@@ -15,7 +15,7 @@ namespace fp6 {
 // a double rounding cannot occur because amax/28 is either exact in fp16 or at least
 // 2^-14 (relative) away from every fp16 midpoint.
 __global__ __launch_bounds__(256) void block_scale_kernel(const uint16_t* __restrict__ W, int64_t N, int64_t K,
-                                                           int64_t block, uint16_t* __restrict__ scales)
+                                                           int64_t block, float fmax, uint16_t* __restrict__ scales)
 {
     const int64_t G = K / block;
     const int64_t n = blockIdx.x / G, g = blockIdx.x % G;
@@ -39,7 +39,7 @@ __global__ __launch_bounds__(256) void block_scale_kernel(const uint16_t* __rest
     if (threadIdx.x == 0) {
         for (unsigned w = 1; w < blockDim.x / 64; w++) amax = max(amax, s_max[w]);
         float a = (float)__builtin_bit_cast(_Float16, (uint16_t)amax);
-        _Float16 S = (_Float16)(a / 28.0f);
+        _Float16 S = (_Float16)(a / fmax);      // 28 for E3M2, 24 for E3M1 (the format's largest magnitude)
         scales[g * N + n] = __builtin_bit_cast(uint16_t, S);
     }
 }
@@ -50,30 +50,33 @@ __global__ __launch_bounds__(256) void block_scale_kernel(const uint16_t* __rest
 // division can move it, and an exact midpoint divides exactly - so rounding q decides
 // exactly as rounding the real quotient would.  On the E3M2 grid the spacing inside
 // the binade of q is 2^(e-2) (1/16 below 0.25), so the rounding is one rint of q/spacing.
+// MB = mantissa bits: 2 for E3M2 (spacing 2^(e-2), largest value 28), 1 for E3M1 (2^(e-1), 24).
+template <int MB = 2>
 __device__ __forceinline__ uint32_t e3m2_code(uint16_t wbits, float S)
 {
-    const uint32_t sign = (wbits >> 15) << 5;
+    const uint32_t sign = (wbits >> 15) << (3 + MB);
     if (S == 0.0f) return sign;
     float a = (float)__builtin_bit_cast(_Float16, (uint16_t)(wbits & 0x7FFFu));
-    float q = fminf(a / S, 28.0f);
+    float q = fminf(a / S, MB == 2 ? 28.0f : 24.0f);
     int e = (int)((__builtin_bit_cast(uint32_t, q) >> 23) & 0xFF) - 127;   // floor(log2 q), q normal
     e = max(e, -2);
-    float inv_step = __builtin_bit_cast(float, (uint32_t)(127 - (e - 2)) << 23);   // 2^-(e-2)
-    float step = __builtin_bit_cast(float, (uint32_t)(127 + (e - 2)) << 23);
+    float inv_step = __builtin_bit_cast(float, (uint32_t)(127 - (e - MB)) << 23);   // 2^-(e-MB)
+    float step = __builtin_bit_cast(float, (uint32_t)(127 + (e - MB)) << 23);
     float v = rintf(q * inv_step) * step;          // exact products (powers of two)
     uint32_t vb = __builtin_bit_cast(uint32_t, v);
     uint32_t mag;
     if (v < 0.25f) {
-        mag = (uint32_t)(v * 16.0f);               // subnormal codes 0..3
+        mag = (uint32_t)(v * (float)(4 << MB));    // subnormal codes 0 .. 2^MB - 1
     } else {
         uint32_t E = ((vb >> 23) & 0xFF) - 124;    // exponent + bias 3
-        mag = (E << 2) | ((vb >> 21) & 3);
+        mag = (E << MB) | ((vb >> (23 - MB)) & ((1u << MB) - 1u));
     }
     return sign | mag;
 }
 
 // One thread = one lane slot of one tile (64 weights): reads its eight 8-element runs of
 // W, quantizes them, and writes its 32 + 16 bytes of the two planes.
+template <int FMT>
 __global__ __launch_bounds__(256) void quantize_pack_kernel(const uint16_t* __restrict__ W, int64_t N, int64_t K,
                                                              int64_t block, const uint16_t* __restrict__ scales,
                                                              uint4* __restrict__ hi, uint4* __restrict__ lo)
@@ -98,33 +101,47 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(const uint16_t* __re
 #pragma unroll
         for (int e = 0; e < 8; e++) {
             uint16_t wb = (uint16_t)((e & 1) ? (w2[e >> 1] >> 16) : (w2[e >> 1] & 0xFFFFu));
-            uint32_t c = e3m2_code(wb, S);
+            constexpr int MB = FMT == kE3M2 ? 2 : 1;
+            uint32_t c = e3m2_code<MB>(wb, S);
             const int grp = e >> 2, j = e & 3;
             const int b = 2 * (j & 1) + (j >> 1);
-            const uint32_t s = c >> 5, ex = (c >> 2) & 7, m = c & 3;
+            const uint32_t s = c >> (3 + MB), ex = (c >> MB) & 7, m = c & ((1u << MB) - 1u);
             h |= (s << grp | ex << (2 + 3 * grp)) << (8 * b);
-            l |= (m << (2 * grp)) << (8 * b);
+            l |= (m << (MB * grp)) << (8 * b);
         }
         hiw[f] = h;
-        low[f >> 1] |= l << (4 * (f & 1));
+        if (FMT == kE3M2) low[f >> 1] |= l << (4 * (f & 1));
+        else low[f >> 2] |= l << (2 * (f & 3));
     }
     uint4* hp = hi + tile * kHiTileVec + lane;
     hp[0] = make_uint4(hiw[0], hiw[1], hiw[2], hiw[3]);
     hp[64] = make_uint4(hiw[4], hiw[5], hiw[6], hiw[7]);
-    lo[tile * kLoTileVec + lane] = make_uint4(low[0], low[1], low[2], low[3]);
+    if (FMT == kE3M2) lo[tile * kLoTileVec + lane] = make_uint4(low[0], low[1], low[2], low[3]);
+    else reinterpret_cast<uint2*>(lo)[tile * 64 + lane] = make_uint2(low[0], low[1]);
 }
 
 // ------------------------------------------------------------------ plane readers
 // code of element e (0..7) of a fragment, from its two dwords (L already shifted by 4*(f&1))
+// MB = 2: L = the fragment's dword of the 2-bit plane shifted right by 4*(f&1); code s eee mm.
+// MB = 1: L = its dword of the 1-bit plane shifted right by 2*(f&3); code s eee m.
+template <int MB = 2>
 __device__ __forceinline__ uint32_t fragment_code(uint32_t H, uint32_t L, int e)
 {
     const int grp = e >> 2, j = e & 3;
     const int b = 2 * (j & 1) + (j >> 1);
     const uint32_t hb = (H >> (8 * b)) & 0xFF, lb = (L >> (8 * b)) & 0xFF;
-    const uint32_t s = (hb >> grp) & 1, ex = (hb >> (2 + 3 * grp)) & 7, m = (lb >> (2 * grp)) & 3;
-    return s << 5 | ex << 2 | m;
+    const uint32_t s = (hb >> grp) & 1, ex = (hb >> (2 + 3 * grp)) & 7, m = (lb >> (MB * grp)) & ((1u << MB) - 1u);
+    return s << (3 + MB) | ex << MB | m;
 }
 
+// the fragment's plane dwords as fragment_code wants them
+template <int FMT>
+__device__ __forceinline__ uint32_t fragment_lo(const TileRaw& r, int f)
+{
+    return FMT == kE3M2 ? tile_lo_dword(r, f) >> (4 * (f & 1)) : r.lo[f >> 2] >> (2 * (f & 3));
+}
+
+template <int FMT>
 __global__ __launch_bounds__(256) void unpack_codes_kernel(const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
                                                             int64_t N, int64_t K, uint8_t* __restrict__ codes)
 {
@@ -135,17 +152,18 @@ __global__ __launch_bounds__(256) void unpack_codes_kernel(const u32x4* __restri
     if (tile >= (N / kTile) * ktiles) return;
     const int64_t nb = tile / ktiles, kb = tile % ktiles;
     const int i = lane & 15, g = lane >> 4;
-    TileRaw r = load_tile(hi, lo, (size_t)tile, lane);
+    constexpr int MB = FMT == kE3M2 ? 2 : 1;
+    TileRaw r = load_tile<FMT>(hi, lo, (size_t)tile, lane);
 #pragma unroll
     for (int f = 0; f < 8; f++) {
         const int64_t n = nb * kTile + (f >> 1) * 16 + i;
         const int64_t k = kb * kTile + (f & 1) * 32 + g * 8;
-        const uint32_t H = tile_hi_dword(r, f), L = tile_lo_dword(r, f) >> (4 * (f & 1));
+        const uint32_t H = tile_hi_dword(r, f), L = fragment_lo<FMT>(r, f);
         uint32_t c0 = 0, c1 = 0;
 #pragma unroll
         for (int e = 0; e < 4; e++) {
-            c0 |= fragment_code(H, L, e) << (8 * e);
-            c1 |= fragment_code(H, L, 4 + e) << (8 * e);
+            c0 |= fragment_code<MB>(H, L, e) << (8 * e);
+            c1 |= fragment_code<MB>(H, L, 4 + e) << (8 * e);
         }
         *reinterpret_cast<uint2*>(codes + n * K + k) = make_uint2(c0, c1);
     }
@@ -153,6 +171,7 @@ __global__ __launch_bounds__(256) void unpack_codes_kernel(const u32x4* __restri
 
 // W_hat = RNE_fp16(S * value(code)): the fp32 product of an 11-bit and a 3-bit
 // significand is exact, so the only rounding is the conversion to fp16.
+template <int FMT>
 __global__ __launch_bounds__(256) void dequantize_kernel(const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
                                                           const uint16_t* __restrict__ scales, int64_t N, int64_t K,
                                                           int64_t block, uint16_t* __restrict__ W_hat)
@@ -164,22 +183,23 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const u32x4* __restrict
     if (tile >= (N / kTile) * ktiles) return;
     const int64_t nb = tile / ktiles, kb = tile % ktiles;
     const int i = lane & 15, g = lane >> 4;
-    TileRaw r = load_tile(hi, lo, (size_t)tile, lane);
+    constexpr int MB = FMT == kE3M2 ? 2 : 1;
+    TileRaw r = load_tile<FMT>(hi, lo, (size_t)tile, lane);
 #pragma unroll
     for (int f = 0; f < 8; f++) {
         const int64_t n = nb * kTile + (f >> 1) * 16 + i;
         const int64_t k = kb * kTile + (f & 1) * 32 + g * 8;
         const float S = (float)__builtin_bit_cast(_Float16, scales[(k / block) * N + n]);
-        const uint32_t H = tile_hi_dword(r, f), L = tile_lo_dword(r, f) >> (4 * (f & 1));
+        const uint32_t H = tile_hi_dword(r, f), L = fragment_lo<FMT>(r, f);
         uint32_t out[4];
 #pragma unroll
         for (int e = 0; e < 8; e++) {
-            const uint32_t c = fragment_code(H, L, e);
-            const uint32_t ex = (c >> 2) & 7, m = c & 3;
+            const uint32_t c = fragment_code<MB>(H, L, e);
+            const uint32_t ex = (c >> MB) & 7, m = (c & ((1u << MB) - 1u)) << (2 - MB);   // mantissa as quarters
             // value = m/16 (subnormal) or (4+m) * 2^(ex-5)
             float mag = ex ? (float)((4 + m) << (ex - 1)) * 0.0625f : (float)m * 0.0625f;
             _Float16 hval = (_Float16)(S * mag);
-            uint32_t hb = __builtin_bit_cast(uint16_t, hval) | ((c >> 5) << 15);
+            uint32_t hb = __builtin_bit_cast(uint16_t, hval) | ((c >> (3 + MB)) << 15);
             if (e & 1) out[e >> 1] |= hb << 16; else out[e >> 1] = hb;
         }
         *reinterpret_cast<uint4*>(W_hat + n * K + k) = make_uint4(out[0], out[1], out[2], out[3]);
@@ -189,28 +209,41 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const u32x4* __restrict
 // ------------------------------------------------------------------ launchers
 static inline unsigned slot_blocks(int64_t N, int64_t K) { return (unsigned)(((N / kTile) * (K / kTile) * 64 + 255) / 256); }
 
-hipError_t launch_quantize_pack(const uint16_t* W, int64_t N, int64_t K, int64_t block, void* hi, void* lo,
+hipError_t launch_quantize_pack(int format, const uint16_t* W, int64_t N, int64_t K, int64_t block, void* hi, void* lo,
                                 uint16_t* scales, hipStream_t stream)
 {
     hipLaunchKernelGGL(block_scale_kernel, dim3((unsigned)(N * (K / block))), dim3(block >= 2048 ? 256 : 64), 0, stream,
-                       W, N, K, block, scales);
-    hipLaunchKernelGGL(quantize_pack_kernel, dim3(slot_blocks(N, K)), dim3(256), 0, stream, W, N, K, block,
-                       (const uint16_t*)scales, (uint4*)hi, (uint4*)lo);
+                       W, N, K, block, format == kE3M2 ? 28.0f : 24.0f, scales);
+    if (format == kE3M2)
+        hipLaunchKernelGGL(quantize_pack_kernel<kE3M2>, dim3(slot_blocks(N, K)), dim3(256), 0, stream, W, N, K, block,
+                           (const uint16_t*)scales, (uint4*)hi, (uint4*)lo);
+    else
+        hipLaunchKernelGGL(quantize_pack_kernel<kE3M1>, dim3(slot_blocks(N, K)), dim3(256), 0, stream, W, N, K, block,
+                           (const uint16_t*)scales, (uint4*)hi, (uint4*)lo);
     return hipGetLastError();
 }
 
-hipError_t launch_unpack_codes(const void* hi, const void* lo, int64_t N, int64_t K, uint8_t* codes, hipStream_t stream)
+hipError_t launch_unpack_codes(int format, const void* hi, const void* lo, int64_t N, int64_t K, uint8_t* codes,
+                               hipStream_t stream)
 {
-    hipLaunchKernelGGL(unpack_codes_kernel, dim3(slot_blocks(N, K)), dim3(256), 0, stream, (const u32x4*)hi,
-                       (const u32x4*)lo, N, K, codes);
+    if (format == kE3M2)
+        hipLaunchKernelGGL(unpack_codes_kernel<kE3M2>, dim3(slot_blocks(N, K)), dim3(256), 0, stream, (const u32x4*)hi,
+                           (const u32x4*)lo, N, K, codes);
+    else
+        hipLaunchKernelGGL(unpack_codes_kernel<kE3M1>, dim3(slot_blocks(N, K)), dim3(256), 0, stream, (const u32x4*)hi,
+                           (const u32x4*)lo, N, K, codes);
     return hipGetLastError();
 }
 
-hipError_t launch_dequantize(const void* hi, const void* lo, const uint16_t* scales, int64_t N, int64_t K,
+hipError_t launch_dequantize(int format, const void* hi, const void* lo, const uint16_t* scales, int64_t N, int64_t K,
                              int64_t block, uint16_t* W_hat, hipStream_t stream)
 {
-    hipLaunchKernelGGL(dequantize_kernel, dim3(slot_blocks(N, K)), dim3(256), 0, stream, (const u32x4*)hi,
-                       (const u32x4*)lo, scales, N, K, block, W_hat);
+    if (format == kE3M2)
+        hipLaunchKernelGGL(dequantize_kernel<kE3M2>, dim3(slot_blocks(N, K)), dim3(256), 0, stream, (const u32x4*)hi,
+                           (const u32x4*)lo, scales, N, K, block, W_hat);
+    else
+        hipLaunchKernelGGL(dequantize_kernel<kE3M1>, dim3(slot_blocks(N, K)), dim3(256), 0, stream, (const u32x4*)hi,
+                           (const u32x4*)lo, scales, N, K, block, W_hat);
     return hipGetLastError();
 }
 
