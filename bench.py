@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the W6A16 fp6_linear hot path on one MI355X.
 
-Workload (BASELINE config 5): a 34B-class decoder stack - 48 layers, hidden 8192, MLP
+Workload (configuration 5 of the benchmark definition): a 34B-class decoder stack - 48 layers, hidden 8192, MLP
 22016, grouped-query attention (k/v projections 1024 x 8192) - with every linear layer
 (q, k, v, o, gate, up, down) run as fp6_linear on its own packed FP6 weight.  One "step"
 is one pass over all 336 linears (24.9 GB of packed weight, so the pass is cold in HBM

@@ -1,4 +1,4 @@
-"""GPU parity at the full sizes of the BASELINE configs, in the launch configuration that
+"""GPU parity at the full sizes of the five benchmark configurations, in the launch configuration that
 bench.py times (plain fp6_linear, automatic plan).  Configs 2-3 are checked on the full
 matrix; configs 4-5 and the paper's kernel-table shapes on sampled output channels (rows
 of W are quantized independently, so the oracle can do any subset of them one by one):
@@ -82,3 +82,45 @@ def test_cfg5_34b_stack_sampled(layer, si, M):
 @pytest.mark.parametrize("si", range(6))
 def test_paper_kernel_table_shapes_batch8_sampled(si):
     _check("paper_table_b1", si, 8, sample=256)
+
+
+# ---- fine-grained scales and FP5 at full sizes (sampled channels; every row is quantized on its own)
+
+def _check_variant(kind, workload, si, M, block=128, sample=192):
+    _, N, K = inputs.WORKLOADS[workload]["shapes"][si]
+    W = inputs.workload_weight(workload, si, layer=0, device=DEV)
+    X = inputs.activation(M, K, seed=inputs.workload_seed(workload, 7000 + si) + M, device=DEV)
+    rng = np.random.default_rng(N * 17 + K)
+    rows = np.sort(rng.choice(N, size=sample, replace=False))
+    rows[0], rows[-1] = 0, N - 1
+    ridx = torch.from_numpy(rows).to(DEV)
+    Wr = to_np16(W[ridx])
+    if kind == "fgq":
+        hi, lo, sc = P.fp6_quantize_pack_fgq(W, block)
+        Y = P.fp6_linear_fgq(X, hi, lo, sc, N, K, block)
+        codes_o, scales_o = O.quantize_fgq(Wr, block)
+        assert np.array_equal(to_np16(sc[:, ridx]), scales_o.T)
+        assert np.array_equal(P.fp6_unpack_codes(hi, lo, N, K)[ridx].cpu().numpy(), codes_o)
+        Yref = O.linear_fgq(to_np16(X), codes_o, scales_o, block)
+    else:
+        hi, lo, sc = P.fp5_quantize_pack(W)
+        Y = P.fp5_linear(X, hi, lo, sc, N, K)
+        codes_o, scales_o = O.quantize5(Wr)
+        assert np.array_equal(to_np16(sc[ridx]), scales_o)
+        assert np.array_equal(P.fp5_unpack_codes(hi, lo, N, K)[ridx].cpu().numpy(), codes_o)
+        Yref = O.linear5(to_np16(X), codes_o, scales_o)
+    torch.cuda.synchronize()
+    assert_y_close(Y[:, ridx], Yref, (kind, workload, si, M))
+
+
+@pytest.mark.parametrize("kind", ["fgq", "fp5"])
+@pytest.mark.parametrize("si", range(6))
+def test_paper_kernel_table_shapes_fgq_and_fp5_sampled(si, kind):
+    _check_variant(kind, "paper_table_b1", si, 8)
+
+
+@pytest.mark.parametrize("kind", ["fgq", "fp5"])
+@pytest.mark.parametrize("M", [1, 512])
+@pytest.mark.parametrize("si", [1, 4, 6])        # k (1024x8192), gate (22016x8192), down (8192x22016)
+def test_cfg5_shapes_fgq_and_fp5_sampled(si, M, kind):
+    _check_variant(kind, "cfg5_34b_stack", si, M, block=256)
