@@ -166,6 +166,9 @@ int fp6_linear(const uint16_t *X, int64_t M, const void *hi_plane, const void *l
  *                       against); 2 = one fp16 multiply by 2^12 per pair of weights.  Same results as
  *                       the bias shift; they exist to measure what it saves.  Not combinable with
  *                       FP6_HINT_WAVES / FP6_HINT_DEPTH.
+ *   FP6_HINT_HALF(x)    decode family: 1 = workgroups own 32 output channels (half a tile) instead of 64,
+ *                       2 = never; row-wise FP6 with the bias-shift unpack and four wavefronts only; with it
+ *                       FP6_HINT_DEPTH may be 4, 6 or 8
  * An unsupported combination returns FP6_ERR_VARIANT.
  */
 #define FP6_HINT_WAVES(w) ((int)(w) << 8)
@@ -173,6 +176,7 @@ int fp6_linear(const uint16_t *X, int64_t M, const void *hi_plane, const void *l
 #define FP6_HINT_BLOCK_M(b) (((int)(b) / 16) << 16)
 #define FP6_HINT_MEET(x) ((int)(x) << 20)
 #define FP6_HINT_DEQUANT(x) ((int)(x) << 22)
+#define FP6_HINT_HALF(x) ((int)(x) << 24)
 size_t fp6_linear_variant_workspace_bytes(int64_t M, int64_t N, int64_t K, int variant, int split_k);
 int fp6_linear_variant(const uint16_t *X, int64_t M, const void *hi_plane, const void *lo_plane,
                        const uint16_t *scales, int64_t N, int64_t K, uint16_t *Y,

@@ -43,7 +43,8 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
     const int64_t ktiles = K / FP6_TILE, nblocks = N / FP6_TILE;
     // tuning hints ride in the upper bits of `variant`; 0 = automatic
     const int hint_waves = (variant >> 8) & 0xF, hint_depth = (variant >> 12) & 0xF, hint_bm = ((variant >> 16) & 0xF) * 16,
-              hint_meet = (variant >> 20) & 0x3, hint_dequant = (variant >> 22) & 0x3;
+              hint_meet = (variant >> 20) & 0x3, hint_dequant = (variant >> 22) & 0x3,
+              hint_half = (variant >> 24) & 0x3;
     variant &= 0xFF;
     if (variant == FP6_VARIANT_AUTO) variant = (M <= 16) ? FP6_VARIANT_DECODE : FP6_VARIANT_GEMM;
     if (variant != FP6_VARIANT_DECODE && variant != FP6_VARIANT_GEMM) return false;
@@ -63,17 +64,35 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
     }
     // the ablations exist for the default kernel configurations only
     if (hint_dequant > 2 || (hint_dequant && (hint_waves || hint_depth))) return false;
+    if (hint_half && variant != FP6_VARIANT_DECODE) return false;
     int64_t tiles, regs_per_tile;
     if (variant == FP6_VARIANT_DECODE) {
-        if ((hint_waves && hint_waves != 4 && hint_waves != 8) || (hint_depth && (hint_depth < 2 || hint_depth > 4)) || hint_bm ||
-            hint_meet > 2)
+        // half-tile workgroups (32 channels): plain FP6 with row scales and the bias-shift unpack only
+        const bool half_ok = format == kE3M2 && !block && !hint_dequant && (!hint_waves || hint_waves == 4) &&
+                             2 * nblocks <= kMaxCounters;
+        if (hint_half > 2 || (hint_half == 1 && !half_ok)) return false;
+        // Measured at M <= 4: half-tile workgroups win where they give one workgroup per compute unit with
+        // no K-split or a two-way one (8192 or 4096 channels: 10.3 against 11.6 us at 8192 x 8192) - the
+        // result then needs no meeting, or a cheap one; with more workgroups per unit they lose.
+        int half_split = 0;
+        if (half_ok && M <= 4 && !hint_depth) {
+            if (2 * nblocks >= 256 && 2 * nblocks <= 288) half_split = 1;
+            else if (4 * nblocks >= 256 && 4 * nblocks <= 288 && ktiles % 2 == 0 && ktiles / 2 >= 8) half_split = 2;
+        }
+        p.half_tiles = hint_half == 1 || (hint_half == 0 && half_split && (!split_k || split_k == half_split));
+        if ((hint_waves && hint_waves != 4 && hint_waves != 8) || hint_bm || hint_meet > 2 ||
+            (hint_depth && !(p.half_tiles ? (hint_depth == 4 || hint_depth == 6 || hint_depth == 8)
+                                          : (hint_depth >= 2 && hint_depth <= 4))))
             return false;
         p.block_m = 16;
         p.waves = hint_waves ? hint_waves : 4;
         p.depth = hint_depth ? hint_depth : 4;
         tiles = nblocks;
         regs_per_tile = 256;                       // float4 per output tile (64 x 16 fp32)
-        p.split_k = split_k ? split_k : pick_decode_split(nblocks, ktiles, p.waves);
+        p.split_k = split_k ? split_k
+                    : (p.half_tiles && half_split) ? half_split
+                    : (p.half_tiles && 2 * nblocks >= 256) ? 1
+                    : pick_decode_split(p.half_tiles ? 2 * nblocks : nblocks, ktiles, p.waves);
         if (block) {
             // the scales of a workgroup's K-slice are staged in LDS, 128 bytes per block of K: keep that under 96 KB
             auto lds = [&](int64_t d) { return (((ktiles / d - 1) >> p.gshift) + 2) * 128; };

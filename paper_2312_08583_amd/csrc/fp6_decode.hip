@@ -222,6 +222,171 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Half-tile workgroups: a workgroup owns 32 output channels (the upper or lower half of the 64
+// that a tile covers) and, wherever that yields enough workgroups, the whole of K - so the result
+// needs no meeting with other workgroups.  Of each tile a lane fetches the 16 bytes of the 4-bit
+// plane and the 8 bytes of the 2-bit plane that belong to its half (fragments 4h .. 4h+3).  The
+// two halves of a block of channels run on the same compute die (ids 8 apart), so the 2-bit plane,
+// whose 16-byte pieces hold both halves, is fetched from HBM once.
+struct HalfRaw {
+    u32x4 hi;
+    u32x2 lo;
+};
+
+__device__ __forceinline__ HalfRaw load_half(const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
+                                             size_t tile_index, int lane, int h)
+{
+    HalfRaw r;
+    r.hi = __builtin_nontemporal_load(hi + tile_index * kHiTileVec + h * 64 + lane);
+    r.lo = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(lo + tile_index * kLoTileVec + lane) + h);
+    return r;
+}
+
+template <int WAVES, int D>
+__global__ __launch_bounds__(WAVES * 64) void decode_half_kernel(
+    const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
+    const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
+    float4v* __restrict__ partials, uint32_t* __restrict__ counters, unsigned long long* __restrict__ slots,
+    int split_k, int pairwise)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int ktiles = K / kTile;
+    // ids b and b + 8 are the two halves of one (block, slice) unit
+    const int h = (blockIdx.x >> 3) & 1;
+    const int unit = (blockIdx.x & 7) + 8 * (blockIdx.x >> 4);
+    if (unit >= (N / kTile) * split_k) return;            // the grid is padded to a multiple of 16
+    const int nb = unit / split_k, s = unit % split_k;
+    const int kt_per = ktiles / split_k;
+    const int kt_end = (s + 1) * kt_per;
+    const int m = lane & 15, g = lane >> 4;
+    const uint16_t* xrow = X + (size_t)min(m, M - 1) * K + g * 8;
+    const size_t tile0 = (size_t)nb * ktiles;
+    const int ch0 = nb * kTile + h * 32;                   // first channel of this workgroup
+
+    half4 sc = half4{0, 0, 0, 0};
+    if ((int)threadIdx.x < 8 * M) sc = *reinterpret_cast<const half4*>(scales + ch0 + (threadIdx.x & 7) * 4);
+
+    float4v acc[2];
+    acc[0] = acc[1] = float4v{0.f, 0.f, 0.f, 0.f};
+    auto mac = [&](const HalfRaw& r, const XFrag& x) {
+#pragma unroll
+        for (int f = 0; f < 4; f++) {
+            half8 w = unpack_fragment<kBiasShift>(r.hi[f], r.lo[f >> 1] >> (4 * (f & 1)));
+            acc[f >> 1] = mfma16x16x32(w, (f & 1) ? x.q1 : x.q0, acc[f >> 1]);
+        }
+    };
+
+    const int kt0 = s * kt_per + wave;
+    const int cnt = (kt_end - kt0 + WAVES - 1) / WAVES;
+    if (cnt > 0) {
+        HalfRaw raw[D];
+        XFrag xf[D];
+#pragma unroll
+        for (int u = 0; u < D - 1; u++) {
+            const int k = kt0 + min(u, cnt - 1) * WAVES;
+            raw[u] = load_half(hi, lo, tile0 + k, lane, h);
+            xf[u] = load_x(xrow, k);
+        }
+        int j0 = 0;
+        for (; j0 + 2 * D - 1 <= cnt; j0 += D) {
+#pragma unroll
+            for (int u = 0; u < D; u++) {
+                const int k = kt0 + (j0 + u + D - 1) * WAVES;
+                raw[(u + D - 1) % D] = load_half(hi, lo, tile0 + k, lane, h);
+                xf[(u + D - 1) % D] = load_x(xrow, k);
+                mac(raw[u], xf[u]);
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < 2 * D - 2; v++) {
+            const int j = j0 + v;
+            if (j < cnt) {
+                if (j + D - 1 < cnt) {
+                    const int k = kt0 + (j + D - 1) * WAVES;
+                    raw[(v + D - 1) % D] = load_half(hi, lo, tile0 + k, lane, h);
+                    xf[(v + D - 1) % D] = load_x(xrow, k);
+                }
+                mac(raw[v % D], xf[v % D]);
+            }
+        }
+    }
+
+    // thread m*8 + (4t + g) takes channels 16t + 4g + r of column m  (t = 0, 1)
+    __shared__ float4v red[WAVES][128];
+    red[wave][lane] = acc[0];
+    red[wave][64 + lane] = acc[1];
+    __syncthreads();
+    const int tid = threadIdx.x;
+    const bool active = tid < 8 * M;
+    const int mm = tid >> 3, n4 = tid & 7;
+    float4v sum = float4v{0.f, 0.f, 0.f, 0.f};
+    if (active) {
+        const int src = (n4 >> 2) * 64 + (n4 & 3) * 16 + mm;
+#pragma unroll
+        for (int w = 0; w < WAVES; w++) sum += red[w][src];
+    }
+    bool keep_lo = active, keep_hi = active;
+    if (split_k > 1 && pairwise) {
+        if (active) {
+            const size_t node = (size_t)32 * M;          // the two halves share their block's tree nodes
+            unsigned long long* mine = slots + (size_t)nb * split_k * node + (h * 8 * M + tid) * 2;
+            Pair p0{sum[0], sum[1]}, p1{sum[2], sum[3]};
+            keep_lo = meet_tree(mine, node, s, split_k, p0);
+            keep_hi = meet_tree(mine + 1, node, s, split_k, p1);
+            sum = float4v{p0.a, p0.b, p1.a, p1.b};
+        }
+    } else if (split_k > 1) {
+        if (active)
+            store_partial(partial_window(partials + ((size_t)nb * split_k + s) * 256, 4096), h * 128 + tid, sum);
+        if (!arrive_last(&counters[(nb * 2 + h) * kCounterStride], (uint32_t)split_k)) return;
+        if (active) {
+            sum = float4v{0.f, 0.f, 0.f, 0.f};
+            for (int ss = 0; ss < split_k; ss += 16) {
+                float4v v[16];
+#pragma unroll
+                for (int u = 0; u < 16; u++) {
+                    const int sl = min(ss + u, split_k - 1);
+                    v[u] = load_partial(partial_window(partials + ((size_t)nb * split_k + sl) * 256, 4096), h * 128 + tid);
+                }
+#pragma unroll
+                for (int u = 0; u < 16; u++)
+                    if (ss + u < split_k) sum += v[u];
+            }
+        }
+    }
+    if (keep_lo || keep_hi) {
+        half4 y;
+#pragma unroll
+        for (int r = 0; r < 4; r++) y[r] = (_Float16)(sum[r] * ((float)sc[r] * 4096.0f));
+        uint16_t* dst = Y + (size_t)mm * N + ch0 + n4 * 4;
+        if (keep_lo && keep_hi) {
+            *reinterpret_cast<half4*>(dst) = y;
+        } else if (keep_lo) {
+            *reinterpret_cast<half2v*>(dst) = half2v{y[0], y[1]};
+        } else {
+            *reinterpret_cast<half2v*>(dst + 2) = half2v{y[2], y[3]};
+        }
+    }
+}
+
+template <int WAVES, int D>
+static hipError_t launch_decode_half_t(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
+                                       const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
+                                       hipStream_t stream)
+{
+    uint32_t* counters = reinterpret_cast<uint32_t*>(workspace);
+    float4v* partials = reinterpret_cast<float4v*>(reinterpret_cast<char*>(workspace) + kZeroBytes);
+    unsigned long long* slots = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(workspace) + kCounterBytes);
+    const int64_t units = (N / kTile) * p.split_k;
+    const unsigned grid = (unsigned)((units + 7) / 8 * 16);
+    hipLaunchKernelGGL((decode_half_kernel<WAVES, D>), dim3(grid), dim3(WAVES * 64), 0, stream, X, (int)M,
+                       (const u32x4*)hi, (const u32x4*)lo, scales, (int)N, (int)K, Y, partials, counters, slots,
+                       p.split_k, p.pairwise);
+    return hipGetLastError();
+}
+
 template <int WAVES, int D, int DQ = kBiasShift, bool FGQ = false, int FMT = kE3M2>
 static hipError_t launch_decode_t(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
                                   const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
@@ -243,6 +408,11 @@ hipError_t launch_decode(const LinearPlan& p, const uint16_t* X, int64_t M, cons
                          const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                          hipStream_t stream)
 {
+    if (p.half_tiles) {
+        if (p.depth == 8) return launch_decode_half_t<4, 8>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        if (p.depth == 6) return launch_decode_half_t<4, 6>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        return launch_decode_half_t<4, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+    }
     if (p.format == kE3M1) return launch_decode_t<4, 4, kBiasShift, false, kE3M1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     if (p.gshift >= 0) return launch_decode_t<4, 4, kBiasShift, true>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     if (p.dequant == kIntRebias) return launch_decode_t<4, 4, kIntRebias>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);

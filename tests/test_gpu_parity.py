@@ -245,6 +245,27 @@ def test_no_bias_shift_ablation_matches_oracle_and_the_bias_shift_path(M, ablati
     assert torch.equal(Ya, Yb)
 
 
+@pytest.mark.parametrize("M", [1, 3, 16])
+@pytest.mark.parametrize("split,meet", [(1, 0), (2, 0), (2, 1), (4, 0), (4, 2), (6, 1)])
+@pytest.mark.parametrize("depth", [0, 8])
+def test_decode_half_tile_workgroups(M, split, meet, depth):
+    # workgroups that own 32 channels: same results as the oracle, whatever the way the K-slices meet
+    N, K = 320, 64 * 24
+    B = P.binding
+    W = inputs.weight(N, K, seed=800 + split, sigma=0.02, outlier_frac=0.001, device=DEV)
+    X = inputs.activation(M, K, seed=810 + M, device=DEV)
+    hi, lo, sc = _quant(W)
+    _, _, Yref = oracle_reference(W, X)
+    variant = P.FP6_VARIANT_DECODE | B.FP6_HINT_HALF(1) | B.FP6_HINT_MEET(meet) | B.FP6_HINT_DEPTH(depth)
+    ws = P.new_workspace(P.fp6_linear_variant_workspace_bytes(M, N, K, P.FP6_VARIANT_DECODE | B.FP6_HINT_MEET(1), max(split, 2)), DEV)
+    Y = P.fp6_linear_variant(X, hi, lo, sc, N, K, variant, split, workspace=ws)
+    assert_y_close(Y, Yref, (M, split, meet))
+    Y2 = P.fp6_linear_variant(X, hi, lo, sc, N, K, variant, split, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y2)
+    assert torch.count_nonzero(ws[:B.FP6_WORKSPACE_ZERO_BYTES]).item() == 0
+
+
 def test_split_and_unsplit_agree_and_workspace_is_reusable():
     N, K, M = 512, 2048, 8
     W = inputs.weight(N, K, seed=31, sigma=0.02, outlier_frac=0.001, device=DEV)
