@@ -309,3 +309,45 @@ def test_llama7b_qkvo_full_matrix(M):
     assert np.array_equal(P.fp6_unpack_codes(hi, lo, N, K).cpu().numpy(), codes_o)
     Y = P.fp6_linear(X, hi, lo, sc, N, K)
     assert_y_close(Y, Yref, M)
+
+
+# ------------------------------------------------------------------ extreme aspect ratios, degenerate inputs
+
+@pytest.mark.parametrize("M,N,K", [(1, 65536, 64), (2, 64, 65536), (16, 64, 64), (2048, 128, 256), (1000, 64, 4096),
+                                   (5, 128, 28672), (1, 24576, 128), (700, 1024, 64)])
+def test_extreme_shapes_vs_oracle(M, N, K):
+    # one tile in one direction and thousands in the other; many row blocks of X; a single tile
+    W = inputs.weight(N, K, seed=2000 + N % 97 + K % 89, sigma=0.02, outlier_frac=0.001, device=DEV)
+    X = inputs.activation(M, K, seed=2100 + M, device=DEV)
+    hi, lo, sc = _quant(W)
+    _, _, Yref = oracle_reference(W, X)
+    Y = P.fp6_linear(X, hi, lo, sc, N, K)
+    torch.cuda.synchronize()
+    assert_y_close(Y, Yref, (M, N, K))
+
+
+@pytest.mark.parametrize("M", [1, 16, 64])
+def test_all_zero_weights_and_zero_rows_give_exact_zeros(M):
+    N, K = 256, 512
+    W = inputs.weight(N, K, seed=5, device=DEV)
+    W[::2] = 0                                   # every other output channel: S = 0
+    X = inputs.activation(M, K, seed=6, device=DEV)
+    hi, lo, sc = _quant(W)
+    Y = P.fp6_linear(X, hi, lo, sc, N, K)
+    torch.cuda.synchronize()
+    assert torch.isfinite(Y).all()
+    assert torch.count_nonzero(Y[:, ::2]).item() == 0
+    assert torch.count_nonzero(Y[:, 1::2]).item() > 0
+    W[:] = 0
+    hi, lo, sc = _quant(W)
+    assert torch.count_nonzero(P.fp6_linear(X, hi, lo, sc, N, K)).item() == 0
+
+
+def test_zero_activations_give_zeros_and_results_do_not_depend_on_stale_output():
+    N, K, M = 192, 384, 9
+    W = inputs.weight(N, K, seed=7, device=DEV)
+    hi, lo, sc = _quant(W)
+    out = torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV)
+    P.fp6_linear(torch.zeros((M, K), dtype=torch.float16, device=DEV), hi, lo, sc, N, K, out=out)
+    torch.cuda.synchronize()
+    assert torch.count_nonzero(out).item() == 0          # every element written, none left NaN
