@@ -153,8 +153,8 @@ int fp6_linear(const uint16_t *X, int64_t M, const void *hi_plane, const void *l
  * results).  variant = FP6_VARIANT_AUTO and split_k = 0 reproduce fp6_linear.
  * split_k must divide K/64.  The workspace needed is fp6_linear_variant_workspace_bytes.
  * Bits 8 and up of `variant` carry optional tuning hints (0 = automatic):
- *   FP6_HINT_WAVES(w)   wavefronts per workgroup: 4 or 8 (gemm family: 4 = one per SIMD, each
- *                       wavefront owning 128 output channels; 8 = two per SIMD, 64 channels each)
+ *   FP6_HINT_WAVES(w)   wavefronts per workgroup, decode family: 4 or 8 (the gemm family always uses 8,
+ *                       two per SIMD, 64 output channels each)
  *   FP6_HINT_DEPTH(d)   tiles in the per-wavefront prefetch ring, decode family: 2..4
  *   FP6_HINT_BLOCK_M(b) rows of X per workgroup, gemm family: 32, 64 or 128
  *   FP6_HINT_MEET(x)    decode family with split_k > 1: 1 = K-slices meet at an arrival counter,

@@ -105,7 +105,7 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
             }
         }
     } else {
-        if ((hint_waves && hint_waves != 4 && hint_waves != 8) || hint_depth || hint_meet ||
+        if ((hint_waves && hint_waves != 8) || hint_depth || hint_meet ||
             (hint_bm && hint_bm != 32 && hint_bm != 64 && hint_bm != 128))
             return false;
         if (M * K * 2 >= ((int64_t)1 << 32)) return false;   // X is addressed with 32-bit lane offsets

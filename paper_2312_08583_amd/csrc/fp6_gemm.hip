@@ -1,391 +1,20 @@
-// Tiled kernel (any M) of the W6A16 linear layer for gfx950.
-//
-// A workgroup computes a BM x 512 block of Y.  Its wavefronts stand side by side along
-// N, each owning WN 64-wide blocks of output channels (WN = 1: eight wavefronts, two per
-// SIMD; WN = 2: four wavefronts, one per SIMD, 128 x 128 results each).  Every packed
-// weight is fetched and padded to fp16 (bias shift, Section 5.2) by exactly one
-// wavefront and goes straight into MFMA operand registers - the dequantized weight never
-// exists in memory.  Only the activations are shared.
-//
-// All global traffic of the main loop is asynchronous DMA into LDS (global_load_lds,
-// 16 bytes per lane, no register staging), into a ring of D stages per workgroup:
-//   - the BM x 64 slice of X for a k tile (read by every wavefront as MFMA operands).
-//     Rows are not padded; the 16-byte chunk c of row r is stored at chunk position
-//     c ^ (r & 7), which keeps the DMA writes and the 128-bit operand reads free of bank
-//     conflicts;
-//   - each wavefront's own 3 KB of packed planes per block of output channels
-//     (lane-linear, exactly the order the planes have in memory).
-// The DMA is issued from inline assembly and waited for with explicit s_waitcnt vmcnt:
-// every step issues the same number of loads per wavefront, so "at most (D-2) groups
-// still in flight" is a constant, and the compiler (which cannot see these loads) has
-// no reason to drain the queue.  One barrier per k tile publishes the landed stage and
-// frees the stage consumed in the previous step.
-//
-// What bounds the loop is LDS bandwidth: every wavefront reads the whole X slice, so a
-// step moves (wavefronts x BM x 128 B) + planes through a 128 B/clk port.  With eight
-// wavefronts at BM = 128 that is 152 KB per 2048 MFMA cycles - the port is saturated
-// by data movement alone; four wavefronts with twice the channels each halve it.
-//
-// The row scale is applied once, after the accumulation (Section 5.2).  K may be split
-// over workgroups; the slices meet in an fp32 workspace exactly as in the decode kernel.
-#include "fp6_common.hpp"
-#include "fp6_internal.hpp"
-#include "fp6_reduce.hpp"
-
-#ifndef FP6_GEMM_HINTS
-#define FP6_GEMM_HINTS 1
-#endif
+// Tiled kernel: dispatch, and the instantiations of the method itself (FP6, bias-shift unpack, row scales).
+#include "fp6_gemm_kernel.hpp"
 
 namespace fp6 {
-
-constexpr int kGemmBlocksN = 8;                               // 64-wide blocks of output channels per workgroup
-constexpr int kWaveTileBytes = kHiTileBytes + kLoTileBytes;   // 3072: the planes of one 64x64 tile
-
-// 16 bytes per lane from (base + lane_offset) to LDS address lds + 16 * lane (lds is wave-uniform).
-// M0 carries the LDS address; nothing else in these kernels uses M0 (gfx9 DS instructions do not),
-// and the compiler does not accept it in a clobber list.
-__device__ __forceinline__ void dma16(const void* base, uint32_t lane_offset, uint32_t lds)
-{
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :
-                 : "v"(lane_offset), "s"(base), "s"(lds)
-                 : "memory");
-}
-
-// 4 bytes per lane from (base + lane_offset) to LDS address lds + 4 * lane.
-__device__ __forceinline__ void dma4(const void* base, uint32_t lane_offset, uint32_t lds)
-{
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
-                 :
-                 : "v"(lane_offset), "s"(base), "s"(lds)
-                 : "memory");
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
-
-// FGQ: one scale per `64 << gshift` elements along K (Section 3, fine-grained quantization).
-// The product sums of the k tiles of one such block are formed in a second accumulator; at
-// the end of the block they are multiplied by the block's scales and added to the running
-// sum - "after matrix multiplication, before the accumulation" (Section 5.2).  The scales of
-// a wavefront's 64 channels (128 bytes per block) ride along with every stage of the DMA ring.
-template <int BM, int D, int WN, int DQ, bool FGQ, int FMT>
-__global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
-    const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
-    const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
-    float4v* __restrict__ partials, uint32_t* __restrict__ counters, int split_k, int gshift)
-{
-    static_assert(!FGQ || (WN == 1 && BM <= 64), "fine-grained scales: two accumulators must fit the register file");
-    constexpr int WAVES = kGemmBlocksN / WN;
-    constexpr int THREADS = WAVES * 64;
-    constexpr int MT = BM / 16;                         // 16-row blocks of X per workgroup
-    constexpr int NT = 4 * WN;                          // 16-channel blocks per wavefront
-    constexpr int XG = BM / 8;                          // 8-row groups (1 KB of DMA each) per stage
-    constexpr int XL = XG >= WAVES ? XG / WAVES : 1;    // X groups moved per wavefront and k tile
-    constexpr int kLoads = XL + 3 * WN + (FGQ ? 1 : 0); // DMA instructions per wavefront and k tile
-    constexpr int kXBytes = BM * kTile * 2;
-    constexpr int kScaleOff = kXBytes + kGemmBlocksN * kWaveTileBytes;     // FGQ: 256 bytes per wavefront
-    constexpr int kStageBytes = kScaleOff + (FGQ ? WAVES * 256 : 0);
-    constexpr int kTileRegs = MT * NT * THREADS;        // float4 per output tile
-    __shared__ __align__(16) unsigned char smem[D * kStageBytes];
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int ktiles = K / kTile, nblocks = N / kTile;
-    const int mblk = (M + BM - 1) / BM;
-    const int nblk = (nblocks + kGemmBlocksN - 1) / kGemmBlocksN;
-    // Workgroups are dealt round-robin to the eight compute dies, each with its own L2.  The
-    // workgroups that read the same planes (same block of weights and K-slice, different rows of
-    // X) get ids that are congruent mod 8, so they run on one die and the planes are fetched
-    // into one L2 once.  The (weight block, K-slice) pairs themselves are spread over all dies.
-    // With at least eight weight blocks it is the blocks that are dealt to the dies (all K-slices
-    // of a block on one die); with fewer, the pairs are, so that no die stays idle.
-    const int xcd = blockIdx.x & 7;
-    int id = blockIdx.x >> 3;
-    const int mb = id % mblk;
-    id /= mblk;
-    int nbw, s;
-    if (nblk >= 8) {
-        s = id % split_k;
-        nbw = (id / split_k) * 8 + xcd;
-        if (nbw >= nblk) return;             // the grid is padded to a multiple of eight blocks
-    } else {
-        const int pair = id * 8 + xcd;
-        if (pair >= nblk * split_k) return;  // ... or of eight pairs
-        nbw = pair / split_k;
-        s = pair % split_k;
-    }
-    const int kt_per = ktiles / split_k;
-    const int kt_begin = s * kt_per, kt_end = kt_begin + kt_per;
-    const int m0 = mb * BM;
-    const int nb0 = nbw * kGemmBlocksN + wave * WN;     // first block of output channels of this wavefront
-    const int i = lane & 15, g = lane >> 4;
-    const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
-
-    // X DMA: this wavefront moves the 8-row groups j = (wave*XL + p) % XG; lane l of a group
-    // fetches row 8j + l/8, chunk (l%8) ^ (l/8), and lands at chunk position l%8.
-    uint32_t xlane[XL], xlds[XL];
-#pragma unroll
-    for (int p = 0; p < XL; p++) {
-        const int j = (wave * XL + p) % XG;
-        int row = m0 + j * 8 + (lane >> 3);
-        row = row < M ? row : M - 1;      // rows past M are computed on valid data and dropped
-        xlane[p] = (uint32_t)row * (uint32_t)K * 2u + (uint32_t)(((lane & 7) ^ (lane >> 3)) * 16);
-        xlds[p] = j * 1024;
-    }
-    const uint32_t wlane = lane * 16;
-    const uint32_t wlds = kXBytes + wave * WN * kWaveTileBytes;
-    // blocks of channels past N are computed on the last valid block and dropped
-    size_t tile0[WN];
-#pragma unroll
-    for (int c = 0; c < WN; c++) tile0[c] = (size_t)min(nb0 + c, nblocks - 1) * ktiles;
-
-    // kLoads DMA instructions per call, always
-    auto issue = [&](int kt, int stage) {
-        const uint32_t sb = smem_base + stage * kStageBytes;
-        const unsigned char* xb = reinterpret_cast<const unsigned char*>(X) + (size_t)kt * (kTile * 2);
-#pragma unroll
-        for (int p = 0; p < XL; p++) dma16(xb, xlane[p], sb + xlds[p]);
-#pragma unroll
-        for (int c = 0; c < WN; c++) {
-            const unsigned char* hb = reinterpret_cast<const unsigned char*>(hi) + (tile0[c] + kt) * kHiTileBytes;
-            const unsigned char* lb = reinterpret_cast<const unsigned char*>(lo) + (tile0[c] + kt) * kLoBytesOf<FMT>;
-            dma16(hb, wlane, sb + wlds + c * kWaveTileBytes);
-            dma16(hb + 1024, wlane, sb + wlds + c * kWaveTileBytes + 1024);
-            // FP5: the 1-bit plane has 512 bytes per tile; the upper lanes fetch them a second time
-            // (into the unused half of the stage's 1 KB) rather than bytes of the next tile
-            dma16(lb, FMT == kE3M2 ? wlane : (wlane & 511u), sb + wlds + c * kWaveTileBytes + 2048);
-        }
-        if (FGQ) {
-            // scales of this tile's block for the wavefront's 64 channels: 128 bytes, fetched by lanes
-            // 0..31 (the upper lanes fetch the same bytes again rather than bytes past the array)
-            const unsigned char* sp = reinterpret_cast<const unsigned char*>(scales) +
-                                      ((size_t)(kt >> gshift) * N + (size_t)min(nb0, nblocks - 1) * kTile) * 2;
-            dma4(sp, (lane & 31) * 4, sb + kScaleOff + wave * 256);
-        }
-    };
-
-    // operand reads: row r = 16a + i, chunk 4q + g, at position (4q + g) ^ (i & 7)
-    const int xoff0 = i * (kTile * 2) + ((g ^ (i & 7)) * 16);
-    const int xoff1 = i * (kTile * 2) + (((4 + g) ^ (i & 7)) * 16);
-
-    float4v acc[MT][NT];
-    float4v part[FGQ ? MT : 1][FGQ ? NT : 1];      // FGQ: product sums of the current block of K
-#pragma unroll
-    for (int a = 0; a < MT; a++)
-#pragma unroll
-        for (int t = 0; t < NT; t++) {
-            acc[a][t] = float4v{0.f, 0.f, 0.f, 0.f};
-            if (FGQ) part[a][t] = float4v{0.f, 0.f, 0.f, 0.f};
-        }
-
-#pragma unroll
-    for (int u = 0; u < D - 1; u++) issue(min(kt_begin + u, kt_end - 1), u);
-
-    // One k tile.  Its DMA was issued D-1 steps ago; D-2 younger groups may stay in flight.  The
-    // stage number u is a compile-time constant (the loop below is unrolled by D), so every LDS
-    // address is a register plus an immediate - a ring indexed at run time measured 10-20% slower.
-    auto step = [&](int kt, int u) {
-        wait_vmcnt<(D - 2) * kLoads>();
-        __syncthreads();          // everyone's DMA landed; everyone is done with the stage refilled next
-        issue(min(kt + D - 1, kt_end - 1), (u + D - 1) % D);
-        const unsigned char* st = smem + u * kStageBytes;
-        const unsigned char* wt = st + wlds;
-        TileRaw raw[WN];
-#pragma unroll
-        for (int c = 0; c < WN; c++) {
-            raw[c].hi0 = *reinterpret_cast<const u32x4*>(wt + c * kWaveTileBytes + wlane);
-            raw[c].hi1 = *reinterpret_cast<const u32x4*>(wt + c * kWaveTileBytes + 1024 + wlane);
-            if (FMT == kE3M2) {
-                raw[c].lo = *reinterpret_cast<const u32x4*>(wt + c * kWaveTileBytes + 2048 + wlane);
-            } else {
-                const u32x2 l = *reinterpret_cast<const u32x2*>(wt + c * kWaveTileBytes + 2048 + lane * 8);
-                raw[c].lo = u32x4{l.x, l.y, 0u, 0u};
-            }
-        }
-#pragma unroll
-        for (int q = 0; q < 2; q++) {
-            half8 xf[MT];
-#pragma unroll
-            for (int a = 0; a < MT; a++) {
-                xf[a] = *reinterpret_cast<const half8*>(st + a * 16 * (kTile * 2) + (q ? xoff1 : xoff0));
-            }
-#pragma unroll
-            for (int t = 0; t < NT; t++) {
-                half8 w = unpack_tile_fragment<DQ, FMT>(raw[t / 4], 2 * (t % 4) + q);
-#pragma unroll
-                for (int a = 0; a < MT; a++) {
-                    if (FGQ) part[a][t] = mfma16x16x32(w, xf[a], part[a][t]);
-                    else acc[a][t] = mfma16x16x32(w, xf[a], acc[a][t]);
-                }
-            }
-        }
-        if (FGQ) {
-            // last tile of a block of K (or of this workgroup's K-slice): scale and accumulate
-            if ((((kt + 1) >> gshift) << gshift) == kt + 1 || kt + 1 == kt_end) {
-#pragma unroll
-                for (int t = 0; t < NT; t++) {
-                    const half4 h = *reinterpret_cast<const half4*>(st + kScaleOff + wave * 256 + (t * 16 + g * 4) * 2);
-#pragma unroll
-                    for (int a = 0; a < MT; a++) {
-#pragma unroll
-                        for (int r = 0; r < 4; r++) acc[a][t][r] += part[a][t][r] * (float)h[r];
-                        part[a][t] = float4v{0.f, 0.f, 0.f, 0.f};
-                    }
-                }
-            }
-        }
-        // Issue order.  The wavefronts of a SIMD leave the barrier together, so they cannot hide
-        // each other's unpack work; instead, after the first fragment, every MFMA (16 cycles in the
-        // matrix pipe) is followed by two of the unpack VALU operations (8 cycles of issue, in its
-        // shadow), and the LDS operand reads of the second k block are spread over the MFMAs of
-        // the first.
-#if FP6_GEMM_HINTS
-        // (tuned for the instruction mix of the FP6 bias-shift unpack; the other variants are left to the compiler,
-        // whose schedule needs fewer registers)
-        if (!FGQ && FMT == kE3M2 && DQ != kHalfMul) {
-        __builtin_amdgcn_sched_group_barrier(0x100, 3 * WN + MT, 0);     // planes + operands of k block 0
-        __builtin_amdgcn_sched_group_barrier(0x002, 15, 0);              // first fragment
-#pragma unroll
-        for (int n = 0; n < 2 * NT * MT; n++) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
-            if (n % 2 == 0 && n >= NT * MT - 2 * MT && n < NT * MT) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-        }
-#endif
-    };
-
-    int kt = kt_begin;
-    for (; kt + D <= kt_end; kt += D) {      // steady state: branch-free trips of D tiles
-#pragma unroll
-        for (int u = 0; u < D; u++) step(kt + u, u);
-    }
-#pragma unroll
-    for (int u = 0; u < D - 1; u++) {        // the last (kt_end - kt_begin) % D tiles
-        if (kt + u < kt_end) step(kt + u, u);
-    }
-    wait_vmcnt<0>();     // the over-fetched ring slots must land before LDS is given back
-    __syncthreads();
-
-    // Everything below is addressed through a copy of the thread index that the compiler cannot
-    // see through, so that none of its address arithmetic is hoisted above the main loop, where it
-    // would take registers the loop needs (and a spilled value reloaded inside the loop makes the
-    // compiler drain the DMA queue).
-    int tid2 = tid;
-    asm volatile("" : "+v"(tid2));
-    const int i2 = tid2 & 15, g2 = (tid2 >> 4) & 3;
-
-    // ---- K-slices of other workgroups
-    if (split_k > 1) {
-        const int tile = nbw * mblk + mb, ntiles = mblk * nblk;
-        {
-            __amdgpu_buffer_rsrc_t win = partial_window(partials + ((size_t)s * ntiles + tile) * kTileRegs, kTileRegs * 16);
-#pragma unroll
-            for (int a = 0; a < MT; a++)
-#pragma unroll
-                for (int t = 0; t < NT; t++) store_partial(win, (a * NT + t) * THREADS + tid2, acc[a][t]);
-        }
-        if (!arrive_last(&counters[tile * kCounterStride], (uint32_t)split_k)) return;
-#pragma unroll
-        for (int a = 0; a < MT; a++)
-#pragma unroll
-            for (int t = 0; t < NT; t++) acc[a][t] = float4v{0.f, 0.f, 0.f, 0.f};
-        for (int ss = 0; ss < split_k; ss++) {
-            __amdgpu_buffer_rsrc_t win = partial_window(partials + ((size_t)ss * ntiles + tile) * kTileRegs, kTileRegs * 16);
-            // sixteen 16-byte loads in flight at a time: more would need registers the main loop
-            // cannot spare
-            constexpr int AG = (MT * NT < 16) ? MT : 16 / NT;
-#pragma unroll
-            for (int a0 = 0; a0 < MT; a0 += AG) {
-                float4v v[AG][NT];
-#pragma unroll
-                for (int a = 0; a < AG; a++)
-#pragma unroll
-                    for (int t = 0; t < NT; t++) v[a][t] = load_partial(win, ((a0 + a) * NT + t) * THREADS + tid2);
-#pragma unroll
-                for (int a = 0; a < AG; a++)
-#pragma unroll
-                    for (int t = 0; t < NT; t++) acc[a0 + a][t] += v[a][t];
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-    }
-
-    // ---- epilogue: lane holds channels n = 16t + 4g + r of row m = 16a + i  (i2, g2 = i, g)
-#pragma unroll
-    for (int c = 0; c < WN; c++) {
-        const int nb = nb0 + c;
-        if (nb >= nblocks) break;
-        float sc[4][4];
-#pragma unroll
-        for (int t = 0; t < 4; t++) {
-            half4 h = half4{1, 1, 1, 1};       // fine-grained scales were applied block by block
-            if (!FGQ) h = *reinterpret_cast<const half4*>(scales + (size_t)nb * kTile + t * 16 + g2 * 4);
-#pragma unroll
-            for (int r = 0; r < 4; r++) sc[t][r] = (float)h[r] * kUnshift<DQ>;
-        }
-#pragma unroll
-        for (int a = 0; a < MT; a++) {
-            const int m = m0 + a * 16 + i2;
-            if (m < M) {
-#pragma unroll
-                for (int t = 0; t < 4; t++) {
-                    half4 y;
-#pragma unroll
-                    for (int r = 0; r < 4; r++) y[r] = (_Float16)(acc[a][c * 4 + t][r] * sc[t][r]);
-                    *reinterpret_cast<half4*>(Y + (size_t)m * N + (size_t)nb * kTile + t * 16 + g2 * 4) = y;
-                }
-            }
-        }
-    }
-}
-
-template <int BM, int D, int WN, int DQ = kBiasShift, bool FGQ = false, int FMT = kE3M2>
-static hipError_t launch_gemm_t(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
-                                const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
-                                hipStream_t stream)
-{
-    uint32_t* counters = reinterpret_cast<uint32_t*>(workspace);
-    float4v* partials = reinterpret_cast<float4v*>(reinterpret_cast<char*>(workspace) + kZeroBytes);
-    const int64_t mblk = (M + BM - 1) / BM, nblk = (N / kTile + kGemmBlocksN - 1) / kGemmBlocksN;
-    const unsigned grid = (unsigned)(nblk >= 8 ? mblk * ((nblk + 7) / 8 * 8) * p.split_k
-                                               : mblk * ((nblk * p.split_k + 7) / 8 * 8));   // padded: see the id mapping
-    hipLaunchKernelGGL((gemm_kernel<BM, D, WN, DQ, FGQ, FMT>), dim3(grid), dim3(kGemmBlocksN / WN * 64), 0, stream, X, (int)M,
-                       (const u32x4*)hi, (const u32x4*)lo, scales, (int)N, (int)K, Y, partials, counters, p.split_k, p.gshift);
-    return hipGetLastError();
-}
 
 hipError_t launch_gemm(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
                        const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                        hipStream_t stream)
 {
-    if (p.format == kE3M1) {
-        if (p.block_m == 32) return launch_gemm_t<32, 4, 1, kBiasShift, false, kE3M1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-        if (p.block_m == 64) return launch_gemm_t<64, 4, 1, kBiasShift, false, kE3M1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-        return launch_gemm_t<128, 3, 1, kBiasShift, false, kE3M1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-    }
-    if (p.gshift >= 0) {
-        if (p.block_m == 32) return launch_gemm_t<32, 4, 1, kBiasShift, true>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-        return launch_gemm_t<64, 4, 1, kBiasShift, true>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-    }
-    switch (p.block_m * 10 + p.waves + p.dequant * 10000) {
-        case 10328: return launch_gemm_t<32, 4, 1, kIntRebias>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-        case 10648: return launch_gemm_t<64, 4, 1, kIntRebias>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-        case 11288: return launch_gemm_t<128, 3, 1, kIntRebias>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-        case 20328: return launch_gemm_t<32, 4, 1, kHalfMul>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-        case 20648: return launch_gemm_t<64, 4, 1, kHalfMul>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-        case 21288: return launch_gemm_t<128, 3, 1, kHalfMul>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-        case 328: return launch_gemm_t<32, 4, 1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-        case 324: return launch_gemm_t<32, 4, 2>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-        case 648: return launch_gemm_t<64, 4, 1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-        case 644: return launch_gemm_t<64, 4, 2>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-        case 1288: return launch_gemm_t<128, 3, 1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-        default: return launch_gemm_t<128, 3, 2>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+    if (p.format != kE3M2 || p.gshift >= 0 || p.dequant != kBiasShift)
+        return launch_gemm_variant(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+    // (The kernel template also supports four wavefronts owning 128 channels each, WN = 2; that shape
+    // measured slower at every block size and is not instantiated.)
+    switch (p.block_m) {
+        case 32: return launch_gemm_t<32, 4, 1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        case 64: return launch_gemm_t<64, 4, 1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        default: return launch_gemm_t<128, 3, 1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     }
 }
 

@@ -51,6 +51,10 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
 hipError_t launch_decode(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
                          const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                          hipStream_t stream);
+// fp6_gemm_variants.hip: plans with an ablation unpack, fine-grained scales or the five-bit format
+hipError_t launch_gemm_variant(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
+                               const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
+                               hipStream_t stream);
 hipError_t launch_gemm(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
                        const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                        hipStream_t stream);
