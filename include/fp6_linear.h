@@ -169,6 +169,8 @@ int fp6_linear(const uint16_t *X, int64_t M, const void *hi_plane, const void *l
  *   FP6_HINT_HALF(x)    decode family: 1 = workgroups own 32 output channels (half a tile) instead of 64,
  *                       2 = never; row-wise FP6 with the bias-shift unpack and four wavefronts only; with it
  *                       FP6_HINT_DEPTH may be 4, 6 or 8
+ *   FP6_HINT_WIDTH(b)   gemm family: 64-channel blocks (= wavefronts) per workgroup, 8 or 4 (row-wise FP6,
+ *                       bias-shift unpack)
  * An unsupported combination returns FP6_ERR_VARIANT.
  */
 #define FP6_HINT_WAVES(w) ((int)(w) << 8)
@@ -177,6 +179,7 @@ int fp6_linear(const uint16_t *X, int64_t M, const void *hi_plane, const void *l
 #define FP6_HINT_MEET(x) ((int)(x) << 20)
 #define FP6_HINT_DEQUANT(x) ((int)(x) << 22)
 #define FP6_HINT_HALF(x) ((int)(x) << 24)
+#define FP6_HINT_WIDTH(b) ((int)(b) << 26)
 size_t fp6_linear_variant_workspace_bytes(int64_t M, int64_t N, int64_t K, int variant, int split_k);
 int fp6_linear_variant(const uint16_t *X, int64_t M, const void *hi_plane, const void *lo_plane,
                        const uint16_t *scales, int64_t N, int64_t K, uint16_t *Y,

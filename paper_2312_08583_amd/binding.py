@@ -45,6 +45,10 @@ def FP6_HINT_HALF(x: int) -> int:
     return int(x) << 24
 
 
+def FP6_HINT_WIDTH(b: int) -> int:
+    return int(b) << 26
+
+
 EXPORTS = ["fp6_layout_version", "fp6_status_string", "fp6_packed_sizes", "fp6_quantize_pack",
            "fp6_unpack_codes", "fp6_dequantize", "fp6_linear_workspace_bytes", "fp6_linear",
            "fp6_linear_variant_workspace_bytes", "fp6_linear_variant", "fp6_quantize_pack_fgq",

@@ -44,7 +44,7 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
     // tuning hints ride in the upper bits of `variant`; 0 = automatic
     const int hint_waves = (variant >> 8) & 0xF, hint_depth = (variant >> 12) & 0xF, hint_bm = ((variant >> 16) & 0xF) * 16,
               hint_meet = (variant >> 20) & 0x3, hint_dequant = (variant >> 22) & 0x3,
-              hint_half = (variant >> 24) & 0x3;
+              hint_half = (variant >> 24) & 0x3, hint_gbn = (variant >> 26) & 0xF;
     variant &= 0xFF;
     if (variant == FP6_VARIANT_AUTO) variant = (M <= 16) ? FP6_VARIANT_DECODE : FP6_VARIANT_GEMM;
     if (variant != FP6_VARIANT_DECODE && variant != FP6_VARIANT_GEMM) return false;
@@ -65,6 +65,15 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
     // the ablations exist for the default kernel configurations only
     if (hint_dequant > 2 || (hint_dequant && (hint_waves || hint_depth))) return false;
     if (hint_half && variant != FP6_VARIANT_DECODE) return false;
+    if (hint_gbn && (variant != FP6_VARIANT_GEMM || format != kE3M2 || block || hint_dequant || hint_waves ||
+                     (hint_gbn != 8 && hint_gbn != 4)))
+        return false;
+    // 64-channel blocks (= wavefronts) per workgroup of the tiled kernel.  Eight share the activations best;
+    // four give twice the workgroups where there are few - at most 32 rows of X, or at most 32 channel blocks
+    // (measured: 40 against 47 us at 32 x 28672 x 8192, 24 against 30 us at 512 x 1024 x 8192).
+    const bool plain = format == kE3M2 && !block && !hint_dequant;
+    const int64_t gbn = hint_gbn ? hint_gbn : (variant == FP6_VARIANT_GEMM && plain && (M <= 32 || nblocks <= 32)) ? 4 : 8;
+    p.gbn = (int)gbn;
     int64_t tiles, regs_per_tile;
     if (variant == FP6_VARIANT_DECODE) {
         // half-tile workgroups (32 channels): plain FP6 with row scales and the bias-shift unpack only
@@ -119,14 +128,15 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
         if (block && hint_bm > 64) return false;        // fine-grained scales: two accumulators per tile
         for (int bm = 32; bm <= (block ? 64 : 128); bm *= 2) {
             if (hint_bm ? bm != hint_bm : (bm > 32 && bm / 2 >= M)) continue;
-            const int64_t mblk = (M + bm - 1) / bm, t = mblk * ((nblocks + 7) / 8);
-            const double step = bm == 128 ? 1.47 : (bm == 64 ? 1.0 : 0.8);
-            const double slice = bm == 128 ? 8.0 : (bm == 64 ? 2.5 : 1.5);
+            const int64_t mblk = (M + bm - 1) / bm, t = mblk * ((nblocks + gbn - 1) / gbn);
+            // (per-tile times and per-slice exchange costs of eight-wavefront workgroups; narrower ones scale)
+            const double step = (bm == 128 ? 1.47 : (bm == 64 ? 1.0 : 0.8)) * (gbn == 8 ? 1.0 : 0.55 * (double)gbn / 4.0);
+            const double slice = (bm == 128 ? 8.0 : (bm == 64 ? 2.5 : 1.5)) * (double)gbn / 8.0;
             for (int64_t d = 1; d <= ktiles && d <= 64; d++) {
                 if (ktiles % d || (split_k && d != split_k)) continue;
                 if (d > 1 && t > kMaxCounters) break;
                 const int64_t wgs = t * d, rounds = (wgs + 255) / 256, resident = wgs < 256 ? wgs : 256;
-                const double hbm_step = 24576.0 * (double)resident / (double)mblk / 5.5e6;
+                const double hbm_step = 3072.0 * (double)gbn * (double)resident / (double)mblk / 5.5e6;
                 const double cost = (double)rounds * ((double)(ktiles / d) * (step > hbm_step ? step : hbm_step) + 6.0 +
                                                       (d > 1 ? 3.0 + (double)d * slice : 0.0));
                 if (best_cost == 0.0 || cost < best_cost) {
@@ -137,9 +147,9 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
             }
         }
         if (best_cost == 0.0) return false;
-        p.depth = p.block_m == 128 ? 3 : 4;
-        tiles = ((M + p.block_m - 1) / p.block_m) * ((nblocks + 7) / 8);
-        regs_per_tile = (int64_t)(p.block_m / 16) * 4 * 512;
+        p.depth = (p.block_m == 128 && gbn == 8) ? 3 : 4;
+        tiles = ((M + p.block_m - 1) / p.block_m) * ((nblocks + gbn - 1) / gbn);
+        regs_per_tile = (int64_t)(p.block_m / 16) * 4 * 64 * gbn;
     }
     if (p.split_k > 1) {
         if (tiles > kMaxCounters) {

@@ -42,7 +42,6 @@
 
 namespace fp6 {
 
-constexpr int kGemmBlocksN = 8;                               // 64-wide blocks of output channels per workgroup
 constexpr int kWaveTileBytes = kHiTileBytes + kLoTileBytes;   // 3072: the planes of one 64x64 tile
 
 // 16 bytes per lane from (base + lane_offset) to LDS address lds + 16 * lane (lds is wave-uniform).
@@ -77,14 +76,16 @@ __device__ __forceinline__ void wait_vmcnt()
 // the end of the block they are multiplied by the block's scales and added to the running
 // sum - "after matrix multiplication, before the accumulation" (Section 5.2).  The scales of
 // a wavefront's 64 channels (128 bytes per block) ride along with every stage of the DMA ring.
-template <int BM, int D, int WN, int DQ, bool FGQ, int FMT>
-__global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
+// GBN = 64-wide blocks of output channels per workgroup: 8 (512 channels), or 4 for launches that would
+// otherwise have too few workgroups.
+template <int BM, int D, int WN, int DQ, bool FGQ, int FMT, int GBN>
+__global__ __launch_bounds__(GBN / WN * 64) void gemm_kernel(
     const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
     const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
     float4v* __restrict__ partials, uint32_t* __restrict__ counters, int split_k, int gshift)
 {
     static_assert(!FGQ || (WN == 1 && BM <= 64), "fine-grained scales: two accumulators must fit the register file");
-    constexpr int WAVES = kGemmBlocksN / WN;
+    constexpr int WAVES = GBN / WN;
     constexpr int THREADS = WAVES * 64;
     constexpr int MT = BM / 16;                         // 16-row blocks of X per workgroup
     constexpr int NT = 4 * WN;                          // 16-channel blocks per wavefront
@@ -92,7 +93,7 @@ __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
     constexpr int XL = XG >= WAVES ? XG / WAVES : 1;    // X groups moved per wavefront and k tile
     constexpr int kLoads = XL + 3 * WN + (FGQ ? 1 : 0); // DMA instructions per wavefront and k tile
     constexpr int kXBytes = BM * kTile * 2;
-    constexpr int kScaleOff = kXBytes + kGemmBlocksN * kWaveTileBytes;     // FGQ: 256 bytes per wavefront
+    constexpr int kScaleOff = kXBytes + GBN * kWaveTileBytes;     // FGQ: 256 bytes per wavefront
     constexpr int kStageBytes = kScaleOff + (FGQ ? WAVES * 256 : 0);
     constexpr int kTileRegs = MT * NT * THREADS;        // float4 per output tile
     __shared__ __align__(16) unsigned char smem[D * kStageBytes];
@@ -101,7 +102,7 @@ __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ktiles = K / kTile, nblocks = N / kTile;
     const int mblk = (M + BM - 1) / BM;
-    const int nblk = (nblocks + kGemmBlocksN - 1) / kGemmBlocksN;
+    const int nblk = (nblocks + GBN - 1) / GBN;
     // Workgroups are dealt round-robin to the eight compute dies, each with its own L2.  The
     // workgroups that read the same planes (same block of weights and K-slice, different rows of
     // X) get ids that are congruent mod 8, so they run on one die and the planes are fetched
@@ -126,7 +127,7 @@ __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
     const int kt_per = ktiles / split_k;
     const int kt_begin = s * kt_per, kt_end = kt_begin + kt_per;
     const int m0 = mb * BM;
-    const int nb0 = nbw * kGemmBlocksN + wave * WN;     // first block of output channels of this wavefront
+    const int nb0 = nbw * GBN + wave * WN;     // first block of output channels of this wavefront
     const int i = lane & 15, g = lane >> 4;
     const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
@@ -349,17 +350,17 @@ __global__ __launch_bounds__(kGemmBlocksN / WN * 64) void gemm_kernel(
     }
 }
 
-template <int BM, int D, int WN, int DQ = kBiasShift, bool FGQ = false, int FMT = kE3M2>
+template <int BM, int D, int WN, int DQ = kBiasShift, bool FGQ = false, int FMT = kE3M2, int GBN = 8>
 static hipError_t launch_gemm_t(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
                                 const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                                 hipStream_t stream)
 {
     uint32_t* counters = reinterpret_cast<uint32_t*>(workspace);
     float4v* partials = reinterpret_cast<float4v*>(reinterpret_cast<char*>(workspace) + kZeroBytes);
-    const int64_t mblk = (M + BM - 1) / BM, nblk = (N / kTile + kGemmBlocksN - 1) / kGemmBlocksN;
+    const int64_t mblk = (M + BM - 1) / BM, nblk = (N / kTile + GBN - 1) / GBN;
     const unsigned grid = (unsigned)(nblk >= 8 ? mblk * ((nblk + 7) / 8 * 8) * p.split_k
                                                : mblk * ((nblk * p.split_k + 7) / 8 * 8));   // padded: see the id mapping
-    hipLaunchKernelGGL((gemm_kernel<BM, D, WN, DQ, FGQ, FMT>), dim3(grid), dim3(kGemmBlocksN / WN * 64), 0, stream, X, (int)M,
+    hipLaunchKernelGGL((gemm_kernel<BM, D, WN, DQ, FGQ, FMT, GBN>), dim3(grid), dim3(GBN / WN * 64), 0, stream, X, (int)M,
                        (const u32x4*)hi, (const u32x4*)lo, scales, (int)N, (int)K, Y, partials, counters, p.split_k, p.gshift);
     return hipGetLastError();
 }

@@ -40,6 +40,7 @@ struct LinearPlan {
     int format;         // 6: FP6 E3M2 (4+2 planes); 5: FP5 E3M1 (4+1 planes)
     int gshift;         // fine-grained scales: log2(block / 64); -1 = one scale per row
     int dequant;        // 0: bias-shift unpack (the method); 1, 2: ablations (integer re-bias, fp16 multiply)
+    int gbn;            // GEMM: 64-channel blocks (= wavefronts) per workgroup: 8 or 4
     int half_tiles;     // DECODE: workgroups own 32 channels (half a tile) instead of 64
     int pairwise;       // DECODE with split_k > 1: K-slices meet pairwise in the slot region (1) or at a counter (0)
 };

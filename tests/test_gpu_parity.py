@@ -266,6 +266,23 @@ def test_decode_half_tile_workgroups(M, split, meet, depth):
     assert torch.count_nonzero(ws[:B.FP6_WORKSPACE_ZERO_BYTES]).item() == 0
 
 
+@pytest.mark.parametrize("width", [8, 4])
+@pytest.mark.parametrize("M,bm,split", [(20, 32, 1), (33, 32, 3), (70, 64, 2), (64, 64, 1), (130, 128, 2), (300, 128, 1)])
+def test_tiled_kernel_workgroup_widths(width, M, bm, split):
+    # workgroups of 8 or 4 wavefronts (512 or 256 output channels); N = 11 channel blocks, so the last
+    # workgroup of either width is ragged
+    N, K = 704, 64 * 12
+    B = P.binding
+    W = inputs.weight(N, K, seed=1700 + width, sigma=0.02, outlier_frac=0.001, device=DEV)
+    X = inputs.activation(M, K, seed=1710 + M, device=DEV)
+    hi, lo, sc = _quant(W)
+    _, _, Yref = oracle_reference(W, X)
+    variant = P.FP6_VARIANT_GEMM | B.FP6_HINT_WIDTH(width) | B.FP6_HINT_BLOCK_M(bm)
+    Y = P.fp6_linear_variant(X, hi, lo, sc, N, K, variant, split)
+    torch.cuda.synchronize()
+    assert_y_close(Y, Yref, (width, M, bm, split))
+
+
 def test_split_and_unsplit_agree_and_workspace_is_reusable():
     N, K, M = 512, 2048, 8
     W = inputs.weight(N, K, seed=31, sigma=0.02, outlier_frac=0.001, device=DEV)
