@@ -74,7 +74,9 @@ typedef enum {
 typedef enum {
     FP6_VARIANT_AUTO = 0,
     FP6_VARIANT_DECODE = 1,  /* M <= 16: one MFMA row block, K split over the wavefronts of a
-                                workgroup (and optionally over workgroups), reduced on chip   */
+                                workgroup (and optionally over workgroups), reduced on chip;
+                                on request also M <= 64 (two or four row blocks per wavefront,
+                                row-wise FP6 without tuning hints)                            */
     FP6_VARIANT_GEMM = 2     /* any M: activations staged in LDS, wavefronts side by side in N */
 } fp6_variant;
 

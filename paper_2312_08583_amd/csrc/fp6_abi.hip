@@ -45,10 +45,17 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
     const int hint_waves = (variant >> 8) & 0xF, hint_depth = (variant >> 12) & 0xF, hint_bm = ((variant >> 16) & 0xF) * 16,
               hint_meet = (variant >> 20) & 0x3, hint_dequant = (variant >> 22) & 0x3,
               hint_half = (variant >> 24) & 0x3, hint_gbn = (variant >> 26) & 0xF;
+    const int variant_hints = variant >> 8;
     variant &= 0xFF;
-    if (variant == FP6_VARIANT_AUTO) variant = (M <= 16) ? FP6_VARIANT_DECODE : FP6_VARIANT_GEMM;
+    if (variant == FP6_VARIANT_AUTO) {
+        // The streaming kernel reads X once per wavefront and tile: unbeatable up to 16 rows, still ahead of the
+        // tiled kernel up to 32 rows on layers of up to 64 M weights (4096 x 4096: 9.6 against 12.8 us), behind it
+        // on larger ones (28672 x 8192: 48 against 40 us), where the tiled kernel's shared X tile pays.
+        const bool stream = M <= 16 || (M <= 32 && format == kE3M2 && !block && !(variant_hints) && N * K <= ((int64_t)1 << 26));
+        variant = stream ? FP6_VARIANT_DECODE : FP6_VARIANT_GEMM;
+    }
     if (variant != FP6_VARIANT_DECODE && variant != FP6_VARIANT_GEMM) return false;
-    if (variant == FP6_VARIANT_DECODE && M > 16) return false;
+    if (variant == FP6_VARIANT_DECODE && M > 64) return false;
     if (split_k < 0 || (split_k > 0 && ktiles % split_k != 0)) return false;
 
     LinearPlan p{};
@@ -93,11 +100,13 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
             (hint_depth && !(p.half_tiles ? (hint_depth == 4 || hint_depth == 6 || hint_depth == 8)
                                           : (hint_depth >= 2 && hint_depth <= 4))))
             return false;
-        p.block_m = 16;
+        // M > 16: the wavefronts take two or four blocks of 16 rows of X (plain FP6, default configuration only)
+        p.block_m = M <= 16 ? 16 : (M <= 32 ? 32 : 64);
+        if (M > 16 && (!plain || hint_waves || hint_depth || p.half_tiles || hint_meet == 2)) return false;
         p.waves = hint_waves ? hint_waves : 4;
         p.depth = hint_depth ? hint_depth : 4;
         tiles = nblocks;
-        regs_per_tile = 256;                       // float4 per output tile (64 x 16 fp32)
+        regs_per_tile = 16 * p.block_m;            // float4 per output tile (64 channels x block_m rows, fp32)
         p.split_k = split_k ? split_k
                     : (p.half_tiles && half_split) ? half_split
                     : (p.half_tiles && 2 * nblocks >= 256) ? 1

@@ -33,13 +33,15 @@ __device__ __forceinline__ XFrag load_x(const uint16_t* __restrict__ xrow, int k
     return x;
 }
 
-template <int DQ, int FMT>
-__device__ __forceinline__ void tile_mac(const TileRaw& r, const XFrag& x, float4v acc[4])
+// One tile against MB blocks of 16 rows of X: every fragment is unpacked once and used MB times.
+template <int DQ, int FMT, int MB>
+__device__ __forceinline__ void tile_mac(const TileRaw& r, const XFrag (&x)[MB], float4v (&acc)[MB][4])
 {
 #pragma unroll
     for (int f = 0; f < 8; f++) {
         half8 w = unpack_tile_fragment<DQ, FMT>(r, f);
-        acc[f >> 1] = mfma16x16x32(w, (f & 1) ? x.q1 : x.q0, acc[f >> 1]);
+#pragma unroll
+        for (int c = 0; c < MB; c++) acc[c][f >> 1] = mfma16x16x32(w, (f & 1) ? x[c].q1 : x[c].q0, acc[c][f >> 1]);
     }
 }
 
@@ -51,7 +53,9 @@ __device__ __forceinline__ void tile_mac(const TileRaw& r, const XFrag& x, float
 // to the running sum - "after matrix multiplication, before the accumulation" (Section 5.2).
 // The scales of the workgroup's 64 channels for its whole K-slice (128 bytes per block) are
 // copied to LDS first, while the first tiles are already on their way.
-template <int WAVES, int D, int DQ, bool FGQ, int FMT>
+// MB = blocks of 16 rows of X handled by every wavefront (M <= 16 * MB).  MB > 1 extends the stream to
+// M <= 64: the weights are still read and unpacked once, X (L2-resident) is read MB times as much.
+template <int WAVES, int D, int DQ, bool FGQ, int FMT, int MB>
 __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
     const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
@@ -64,17 +68,22 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     const int nb = blockIdx.x / split_k, s = blockIdx.x % split_k;
     const int kt_per = ktiles / split_k;
     const int kt_end = (s + 1) * kt_per;
+    static_assert(MB == 1 || !FGQ, "several row blocks: row-wise scales only");
     const int m = lane & 15, g = lane >> 4;
-    const uint16_t* xrow = X + (size_t)min(m, M - 1) * K + g * 8;
+    const uint16_t* xrow[MB];
+#pragma unroll
+    for (int c = 0; c < MB; c++) xrow[c] = X + (size_t)min(16 * c + m, M - 1) * K + g * 8;
     const size_t tile0 = (size_t)nb * ktiles;
 
     // row scales of the four channels this thread will store (fetched early: the epilogue is latency-bound)
     half4 sc = half4{1, 1, 1, 1};
-    if (!FGQ && (int)threadIdx.x < 16 * M) sc = *reinterpret_cast<const half4*>(scales + nb * kTile + (threadIdx.x & 15) * 4);
+    if (!FGQ && (int)threadIdx.x < 256) sc = *reinterpret_cast<const half4*>(scales + nb * kTile + (threadIdx.x & 15) * 4);
 
-    float4v acc[4];
+    float4v acc[MB][4];
 #pragma unroll
-    for (int t = 0; t < 4; t++) acc[t] = float4v{0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < MB; c++)
+#pragma unroll
+        for (int t = 0; t < 4; t++) acc[c][t] = float4v{0.f, 0.f, 0.f, 0.f};
 
     // FGQ: this workgroup's scales -> LDS (16-byte pieces; piece c = block group0 + c/8, channels 8*(c%8)..+7),
     // four loads per thread in flight
@@ -102,23 +111,27 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     const int cnt = (kt_end - kt0 + WAVES - 1) / WAVES;
     if (cnt > 0) {
         TileRaw raw[D];
-        XFrag xf[D];
+        XFrag xf[D][MB];
+        auto fetch_x = [&](int slot, int k) {
+#pragma unroll
+            for (int c = 0; c < MB; c++) xf[slot][c] = load_x(xrow[c], k);
+        };
         // k = the tile's index along K
         auto mac = [&](int slot, int k) {
             if (FGQ) {
-                float4v part[4];
+                float4v part[MB][4];
 #pragma unroll
-                for (int t = 0; t < 4; t++) part[t] = float4v{0.f, 0.f, 0.f, 0.f};
-                tile_mac<DQ, FMT>(raw[slot], xf[slot], part);
+                for (int t = 0; t < 4; t++) part[0][t] = float4v{0.f, 0.f, 0.f, 0.f};
+                tile_mac<DQ, FMT, MB>(raw[slot], xf[slot], part);
                 const uint16_t* sg = gscale + ((k >> gshift) - group0) * kTile + g * 4;
 #pragma unroll
                 for (int t = 0; t < 4; t++) {
                     const half4 sv = *reinterpret_cast<const half4*>(sg + 16 * t);
 #pragma unroll
-                    for (int r = 0; r < 4; r++) acc[t][r] += part[t][r] * (float)sv[r];
+                    for (int r = 0; r < 4; r++) acc[0][t][r] += part[0][t][r] * (float)sv[r];
                 }
             } else {
-                tile_mac<DQ, FMT>(raw[slot], xf[slot], acc);
+                tile_mac<DQ, FMT, MB>(raw[slot], xf[slot], acc);
             }
         };
 
@@ -127,7 +140,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
         for (int u = 0; u < D - 1; u++) {
             const int k = kt0 + min(u, cnt - 1) * WAVES;
             raw[u] = load_tile<FMT>(hi, lo, tile0 + k, lane);
-            xf[u] = load_x(xrow, k);
+            fetch_x(u, k);
         }
         // steady state, branch-free: D tiles per trip, each step refills the slot freed one step ago
         int j0 = 0;
@@ -136,7 +149,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
             for (int u = 0; u < D; u++) {
                 const int k = kt0 + (j0 + u + D - 1) * WAVES;
                 raw[(u + D - 1) % D] = load_tile<FMT>(hi, lo, tile0 + k, lane);
-                xf[(u + D - 1) % D] = load_x(xrow, k);
+                fetch_x((u + D - 1) % D, k);
                 mac(u, kt0 + (j0 + u) * WAVES);
             }
         }
@@ -148,7 +161,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
                 if (j + D - 1 < cnt) {
                     const int k = kt0 + (j + D - 1) * WAVES;
                     raw[(v + D - 1) % D] = load_tile<FMT>(hi, lo, tile0 + k, lane);
-                    xf[(v + D - 1) % D] = load_x(xrow, k);
+                    fetch_x((v + D - 1) % D, k);
                 }
                 mac(v % D, kt0 + j * WAVES);
             }
@@ -157,71 +170,87 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
 
     // ---- add the wavefronts' partial sums in LDS
     // MFMA result layout: lane 16g + m of accumulator t holds channels 16t + 4g + r (r = 0..3)
-    // of column m.  Thread m*16 + (4t + g) takes that value, so the threads of the M valid
+    // of column m.  Thread m*16 + (4t + g) takes that value, so the threads of the valid
     // columns come first and a column's 64 channels sit in 16 consecutive threads.
     __shared__ float4v red[WAVES][256];
-#pragma unroll
-    for (int t = 0; t < 4; t++) red[wave][t * 64 + lane] = acc[t];
-    __syncthreads();
     const int tid = threadIdx.x;
-    const bool active = tid < 16 * M;            // M <= 16, so at most 256 threads
     const int mm = tid >> 4, n4 = tid & 15;
-    float4v sum = float4v{0.f, 0.f, 0.f, 0.f};
-    if (active) {
-        const int src = (n4 >> 2) * 64 + (n4 & 3) * 16 + mm;
+    float4v sum[MB];
+    bool active[MB];
 #pragma unroll
-        for (int w = 0; w < WAVES; w++) sum += red[w][src];
+    for (int c = 0; c < MB; c++) {
+        if (c) __syncthreads();                      // everyone has read the previous block's sums
+#pragma unroll
+        for (int t = 0; t < 4; t++) red[wave][t * 64 + lane] = acc[c][t];
+        __syncthreads();
+        active[c] = tid < 16 * (M - 16 * c);         // rows 16c .. of X that exist (tid < 256 follows)
+        if (MB > 1) active[c] = active[c] && tid < 256;
+        sum[c] = float4v{0.f, 0.f, 0.f, 0.f};
+        if (active[c]) {
+            const int src = (n4 >> 2) * 64 + (n4 & 3) * 16 + mm;
+#pragma unroll
+            for (int w = 0; w < WAVES; w++) sum[c] += red[w][src];
+        }
     }
 
     // ---- add the K-slices of other workgroups
-    bool keep_lo = active, keep_hi = active;     // which halves of `sum` this thread finishes
-    if (split_k > 1 && pairwise) {
+    bool keep_lo = active[0], keep_hi = active[0];     // pairwise meeting: which halves of `sum` this thread finishes
+    if (split_k > 1 && pairwise && MB == 1) {
         // pairwise meeting, two values per slot: thread tid owns slots 2*tid and 2*tid + 1 of a node
-        if (active) {
+        if (active[0]) {
             const size_t node = (size_t)32 * M;          // 64-bit slots per tree node
             unsigned long long* mine = slots + (size_t)nb * split_k * node + tid * 2;
-            Pair p0{sum[0], sum[1]}, p1{sum[2], sum[3]};
+            Pair p0{sum[0][0], sum[0][1]}, p1{sum[0][2], sum[0][3]};
             keep_lo = meet_tree(mine, node, s, split_k, p0);
             keep_hi = meet_tree(mine + 1, node, s, split_k, p1);
-            sum = float4v{p0.a, p0.b, p1.a, p1.b};
+            sum[0] = float4v{p0.a, p0.b, p1.a, p1.b};
         }
     } else if (split_k > 1) {
         // meeting at a counter: the last arrival adds all slices in slice order
-        if (active) store_partial(partial_window(partials + ((size_t)nb * split_k + s) * 256, 4096), tid, sum);
-        if (!arrive_last(&counters[nb * kCounterStride], (uint32_t)split_k)) return;
-        if (active) {
-            sum = float4v{0.f, 0.f, 0.f, 0.f};
-            // up to sixteen slices in flight at a time
-            for (int ss = 0; ss < split_k; ss += 16) {
-                float4v v[16];
+        constexpr uint32_t kSliceBytes = 4096u * MB;
 #pragma unroll
-                for (int u = 0; u < 16; u++) {
+        for (int c = 0; c < MB; c++)
+            if (active[c])
+                store_partial(partial_window(partials + ((size_t)nb * split_k + s) * (256 * MB), kSliceBytes), c * 256 + tid, sum[c]);
+        if (!arrive_last(&counters[nb * kCounterStride], (uint32_t)split_k)) return;
+#pragma unroll
+        for (int c = 0; c < MB; c++) {
+            if (!active[c]) continue;
+            sum[c] = float4v{0.f, 0.f, 0.f, 0.f};
+            // up to sixteen slices in flight at a time
+            constexpr int G = MB == 1 ? 16 : 8;
+            for (int ss = 0; ss < split_k; ss += G) {
+                float4v v[G];
+#pragma unroll
+                for (int u = 0; u < G; u++) {
                     const int sl = min(ss + u, split_k - 1);
-                    v[u] = load_partial(partial_window(partials + ((size_t)nb * split_k + sl) * 256, 4096), tid);
+                    v[u] = load_partial(partial_window(partials + ((size_t)nb * split_k + sl) * (256 * MB), kSliceBytes), c * 256 + tid);
                 }
 #pragma unroll
-                for (int u = 0; u < 16; u++)
-                    if (ss + u < split_k) sum += v[u];
+                for (int u = 0; u < G; u++)
+                    if (ss + u < split_k) sum[c] += v[u];
             }
         }
     }
 
     // ---- epilogue: 16 consecutive threads store the 64 channels of one row of Y
-    if (keep_lo || keep_hi) {
+#pragma unroll
+    for (int c = 0; c < MB; c++) {
+        const bool lo_ok = c ? active[c] : keep_lo, hi_ok = c ? active[c] : keep_hi;
+        if (!(lo_ok || hi_ok)) continue;
         half4 y;
 #pragma unroll
-        for (int r = 0; r < 4; r++) y[r] = (_Float16)(sum[r] * ((float)sc[r] * kUnshift<DQ>));
-        uint16_t* dst = Y + (size_t)mm * N + nb * kTile + n4 * 4;
-        if (keep_lo && keep_hi) {
+        for (int r = 0; r < 4; r++) y[r] = (_Float16)(sum[c][r] * ((float)sc[r] * kUnshift<DQ>));
+        uint16_t* dst = Y + (size_t)(16 * c + mm) * N + nb * kTile + n4 * 4;
+        if (lo_ok && hi_ok) {
             *reinterpret_cast<half4*>(dst) = y;
-        } else if (keep_lo) {
+        } else if (lo_ok) {
             *reinterpret_cast<half2v*>(dst) = half2v{y[0], y[1]};
         } else {
             *reinterpret_cast<half2v*>(dst + 2) = half2v{y[2], y[3]};
         }
     }
 }
-
 
 // ---------------------------------------------------------------------------------------------
 // Half-tile workgroups: a workgroup owns 32 output channels (the upper or lower half of the 64
@@ -387,7 +416,7 @@ static hipError_t launch_decode_half_t(const LinearPlan& p, const uint16_t* X, i
     return hipGetLastError();
 }
 
-template <int WAVES, int D, int DQ = kBiasShift, bool FGQ = false, int FMT = kE3M2>
+template <int WAVES, int D, int DQ = kBiasShift, bool FGQ = false, int FMT = kE3M2, int MB = 1>
 static hipError_t launch_decode_t(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
                                   const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                                   hipStream_t stream)
@@ -398,7 +427,7 @@ static hipError_t launch_decode_t(const LinearPlan& p, const uint16_t* X, int64_
     const unsigned grid = (unsigned)((N / kTile) * p.split_k);
     // FGQ: 128 bytes of scales per block of K in a workgroup's slice (a slice may start inside a block)
     const size_t lds = FGQ ? (size_t)(((K / kTile / p.split_k - 1) >> p.gshift) + 2) * 128 : 0;
-    hipLaunchKernelGGL((decode_kernel<WAVES, D, DQ, FGQ, FMT>), dim3(grid), dim3(WAVES * 64), lds, stream, X, (int)M,
+    hipLaunchKernelGGL((decode_kernel<WAVES, D, DQ, FGQ, FMT, MB>), dim3(grid), dim3(WAVES * 64), lds, stream, X, (int)M,
                        (const u32x4*)hi, (const u32x4*)lo, scales, (int)N, (int)K, Y, partials, counters, slots,
                        p.split_k, p.pairwise, p.gshift);
     return hipGetLastError();
@@ -408,6 +437,8 @@ hipError_t launch_decode(const LinearPlan& p, const uint16_t* X, int64_t M, cons
                          const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                          hipStream_t stream)
 {
+    if (p.block_m == 32) return launch_decode_t<4, 4, kBiasShift, false, kE3M2, 2>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+    if (p.block_m == 64) return launch_decode_t<4, 3, kBiasShift, false, kE3M2, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     if (p.half_tiles) {
         if (p.depth == 8) return launch_decode_half_t<4, 8>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
         if (p.depth == 6) return launch_decode_half_t<4, 6>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);

@@ -65,7 +65,7 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert L.fp6_linear(a + 2, 1, a, a, a, 64, 64, a, None, 0, None) == -3
     assert L.fp6_dequantize(a, a + 8, a, 64, 64, a, None) == -3
     # variant / split requests
-    assert L.fp6_linear_variant(a, 17, a, a, a, 64, 64, a, None, 0, None, B.FP6_VARIANT_DECODE, 0) == -5
+    assert L.fp6_linear_variant(a, 65, a, a, a, 64, 64, a, None, 0, None, B.FP6_VARIANT_DECODE, 0) == -5
     assert L.fp6_linear_variant(a, 1, a, a, a, 64, 256, a, None, 0, None, B.FP6_VARIANT_DECODE, 3) == -5
     assert L.fp6_linear_variant(a, 1, a, a, a, 64, 256, a, None, 0, None, 7, 0) == -5
     # workspace: a split needs one

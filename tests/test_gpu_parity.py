@@ -283,6 +283,24 @@ def test_tiled_kernel_workgroup_widths(width, M, bm, split):
     assert_y_close(Y, Yref, (width, M, bm, split))
 
 
+@pytest.mark.parametrize("M", [17, 24, 32, 33, 47, 48, 64])
+@pytest.mark.parametrize("split", [1, 2, 6])
+def test_decode_family_with_several_row_blocks(M, split):
+    # the streaming kernel with two or four blocks of 16 rows of X per wavefront (M <= 64)
+    N, K = 192, 64 * 24
+    W = inputs.weight(N, K, seed=1800 + split, sigma=0.02, outlier_frac=0.001, device=DEV)
+    X = inputs.activation(M, K, seed=1810 + M, device=DEV)
+    hi, lo, sc = _quant(W)
+    _, _, Yref = oracle_reference(W, X)
+    out = torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV)
+    ws = P.new_workspace(P.fp6_linear_variant_workspace_bytes(M, N, K, P.FP6_VARIANT_DECODE, split), DEV)
+    Y = P.fp6_linear_variant(X, hi, lo, sc, N, K, P.FP6_VARIANT_DECODE, split, out=out, workspace=ws)
+    assert_y_close(Y, Yref, (M, split))
+    Y2 = P.fp6_linear_variant(X, hi, lo, sc, N, K, P.FP6_VARIANT_DECODE, split, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y2)
+
+
 def test_split_and_unsplit_agree_and_workspace_is_reusable():
     N, K, M = 512, 2048, 8
     W = inputs.weight(N, K, seed=31, sigma=0.02, outlier_frac=0.001, device=DEV)
