@@ -166,6 +166,8 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
             p.split_k = 1;
         }
     }
+    // the launch grid is tiles * split_k workgroups (doubled for half tiles, padded to a multiple of 16)
+    if (tiles * p.split_k > ((int64_t)1 << 29)) return false;
     if (p.split_k > 1) {
         // Decode: two slices meet pairwise (one memory round trip instead of three) if the tree nodes,
         // 256 * M bytes each, fit the slot region; deeper trees measured slower than the counter.
@@ -193,6 +195,7 @@ static int quantize_pack_any(int format, const uint16_t* W, int64_t N, int64_t K
 {
     if (!W || !hi_plane || !lo_plane || !scales) return FP6_ERR_NULL;
     if (!shape_ok(N, K) || (block && !block_ok(K, block))) return FP6_ERR_SHAPE;
+    if (block && N * (K / block) > ((int64_t)1 << 30)) return FP6_ERR_SHAPE;      // one workgroup per scale
     if (!aligned16(W) || !aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(scales)) return FP6_ERR_ALIGN;
     return launch_quantize_pack(format, W, N, K, block ? block : K, hi_plane, lo_plane, scales, (hipStream_t)stream) ==
                    hipSuccess
@@ -247,7 +250,7 @@ const char* fp6_status_string(int status)
     switch (status) {
         case FP6_OK: return "ok";
         case FP6_ERR_NULL: return "a required pointer is NULL";
-        case FP6_ERR_SHAPE: return "M, N, K must be positive and N, K multiples of 64";
+        case FP6_ERR_SHAPE: return "M, N, K must be positive, N and K multiples of 64, a scale block 64 * 2^j dividing K";
         case FP6_ERR_ALIGN: return "buffer pointers must be 16-byte aligned";
         case FP6_ERR_WORKSPACE: return "workspace missing or too small";
         case FP6_ERR_VARIANT: return "kernel variant or split_k not valid for this shape";

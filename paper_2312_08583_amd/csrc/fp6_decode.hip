@@ -1,4 +1,5 @@
-// Decode-shape kernel (M <= 16) of the W6A16 linear layer for gfx950.
+// Streaming (decode-shape) kernels of the W6A16 linear layer for gfx950: M <= 16, and up to 64 rows
+// with several row blocks per wavefront.
 //
 // The work is a stream over the packed weight (0.75 byte per weight, Section 5.1):
 // a workgroup owns 64 output channels and one K-slice; its wavefronts take the slice's
@@ -52,7 +53,7 @@ __device__ __forceinline__ void tile_mac(const TileRaw& r, const XFrag (&x)[MB],
 // formed in a zeroed accumulator and multiplied by the block's scales while they are added
 // to the running sum - "after matrix multiplication, before the accumulation" (Section 5.2).
 // The scales of the workgroup's 64 channels for its whole K-slice (128 bytes per block) are
-// copied to LDS first, while the first tiles are already on their way.
+// copied to LDS before the stream starts (one short wait at the head of the kernel).
 // MB = blocks of 16 rows of X handled by every wavefront (M <= 16 * MB).  MB > 1 extends the stream to
 // M <= 64: the weights are still read and unpacked once, X (L2-resident) is read MB times as much.
 template <int WAVES, int D, int DQ, bool FGQ, int FMT, int MB>
@@ -64,7 +65,6 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int ktiles = K / kTile;
-    const int nblocks = N / kTile;
     const int nb = blockIdx.x / split_k, s = blockIdx.x % split_k;
     const int kt_per = ktiles / split_k;
     const int kt_end = (s + 1) * kt_per;
