@@ -129,6 +129,33 @@ def main():
                       gbs=0.75 * weights_per_pass / (ms * 1e-3) / 1e9,
                       tflops=2.0 * M * weights_per_pass / (ms * 1e-3) / 1e12)
 
+    # ---- per-shape breakdown: the same launches grouped by shape (each shape over its `layers` distinct weights,
+    # so every launch is cold), to show which kernel instance sits where against its roofline
+    per_shape = {}
+    for M in legs:
+        xs = {K: inputs.activation(M, K, seed=inputs.workload_seed(WORKLOAD, 9000 + M + K), device=dev)
+              for K in sorted({K for (_, _, K) in shapes})}
+        need = max(P.fp6_linear_workspace_bytes(M, N, K) for (_, N, K) in shapes)
+        ws = P.new_workspace(max(need, 16), dev)
+        rows = []
+        for si, (name, N, K) in enumerate(shapes):
+            y = torch.empty((M, N), dtype=torch.float16, device=dev)
+
+            def sweep():
+                for mats in stack:
+                    _, _, hi, lo, sc = mats[si]
+                    P.fp6_linear(xs[K], hi, lo, sc, N, K, out=y, workspace=ws)
+            us = time_passes(sweep, max(3, args.steps // 4), 1) * 1e3 / len(stack)
+            row = {"shape": "%s %dx%d" % (name, N, K), "us": round(us, 2)}
+            if M <= 118:
+                row["GB/s"] = round(0.75 * N * K / us / 1e3, 1)
+                row["frac"] = round(0.75 * N * K / us / 1e3 / HBM_PEAK_GBS, 3)
+            else:
+                row["TFLOP/s"] = round(2.0 * M * N * K / us / 1e6, 1)
+                row["frac"] = round(2.0 * M * N * K / us / 1e6 / MFMA_FP16_PEAK_TFLOPS, 3)
+            rows.append(row)
+        per_shape["M%d" % M] = rows
+
     # ---- extra leg: projections that read the same input concatenated along N, as inference engines
     # store them (q,k,v -> one [10240, 8192] weight; gate,up -> one [44032, 8192]).  Row scales are per
     # output channel and tiles are ordered by channel block, so the concatenated planes and scales ARE the
@@ -322,6 +349,7 @@ def main():
                        "roofline": {"bound": "mfma", "achieved": r["tflops"], "peak": MFMA_FP16_PEAK_TFLOPS,
                                     "unit": "TFLOP/s", "frac": r["tflops"] / MFMA_FP16_PEAK_TFLOPS, "traffic": traffic.get(512),
                                     "kernel": "gemm_kernel (block_m 128), all %d launches of a step" % launches}}
+    out["per_shape"] = per_shape
     if fused is not None:
         out["fused_projections"] = fused
     if ablation is not None:

@@ -2,9 +2,9 @@
 // Included by the translation units that instantiate it (fp6_gemm.hip: the FP6 bias-shift kernels;
 // fp6_gemm_variants.hip: ablations, fine-grained scales, FP5).
 //
-// A workgroup computes a BM x 512 block of Y.  Its wavefronts stand side by side along
-// N, each owning WN 64-wide blocks of output channels (WN = 1: eight wavefronts, two per
-// SIMD; WN = 2: four wavefronts, one per SIMD, 128 x 128 results each).  Every packed
+// A workgroup computes a BM x (64 * GBN) block of Y, GBN = 8 or 4.  Its wavefronts stand side by
+// side along N, each owning WN 64-wide blocks of output channels (WN = 1 in every instantiated
+// kernel: one wavefront per 64 channels, two per SIMD at GBN = 8).  Every packed
 // weight is fetched and padded to fp16 (bias shift, Section 5.2) by exactly one
 // wavefront and goes straight into MFMA operand registers - the dequantized weight never
 // exists in memory.  Only the activations are shared.
@@ -23,10 +23,10 @@
 // no reason to drain the queue.  One barrier per k tile publishes the landed stage and
 // frees the stage consumed in the previous step.
 //
-// What bounds the loop is LDS bandwidth: every wavefront reads the whole X slice, so a
-// step moves (wavefronts x BM x 128 B) + planes through a 128 B/clk port.  With eight
-// wavefronts at BM = 128 that is 152 KB per 2048 MFMA cycles - the port is saturated
-// by data movement alone; four wavefronts with twice the channels each halve it.
+// LDS traffic per k tile: every wavefront reads the whole X slice (wavefronts x BM x 128 B) plus its
+// planes - at BM = 128 about 152 KB per 2048 MFMA cycles of a SIMD, some 60 % of the 128 B/clk port.
+// Measured, the loop runs the matrix pipe 40-50 % of the time at BM = 128 (the chip is power-limited
+// there) and less at smaller BM, where a k tile holds too few MFMAs per barrier.
 //
 // The row scale is applied once, after the accumulation (Section 5.2).  K may be split
 // over workgroups; the slices meet in an fp32 workspace exactly as in the decode kernel.
