@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--legs", default="1,512", help="comma-separated M values to time")
     ap.add_argument("--no-fused", action="store_true",
                     help="skip the extra leg with q,k,v and gate,up concatenated along N (4 launches per layer)")
+    ap.add_argument("--no-layout2", action="store_true",
+                    help="skip the extra leg with the planes in layout 2 (hardware E3M2 -> fp16 conversion)")
     ap.add_argument("--no-ablation", action="store_true",
                     help="skip the bias-shift ablation on the paper's kernel-table shapes")
     ap.add_argument("--copy-probe", action="store_true",
@@ -192,6 +194,37 @@ def main():
                                  "unit": "TFLOP/s",
                                  "frac": 2.0 * M * weights_per_pass / (ms * 1e-3) / 1e12 / MFMA_FP16_PEAK_TFLOPS})
         del fstack
+
+    # ---- extra leg: the same stack with the planes in layout 2 (4+2 planes arranged so that they merge into
+    # the operand of gfx950's packed E3M2 -> fp16 conversion; same codes, scales and bytes)
+    layout2 = None
+    if not args.no_layout2:
+        stack2 = []
+        for layer in range(layers):
+            mats = []
+            for si, (_, N, K) in enumerate(shapes):
+                W = inputs.workload_weight(WORKLOAD, si, layer=layer, device=dev)
+                hi, lo, sc = P.fp6_quantize_pack_v2(W)
+                mats.append((N, K, hi, lo, sc))
+                del W
+            stack2.append(mats)
+        layout2 = {"what": "planes in layout 2: merged in registers and converted by v_cvt_scalef32_pk32_f16_bf6"}
+        for M in legs:
+            xs = {K: inputs.activation(M, K, seed=inputs.workload_seed(WORKLOAD, 9000 + M + K), device=dev)
+                  for K in sorted({K for (_, _, K) in shapes})}
+            ys = {N: torch.empty((M, N), dtype=torch.float16, device=dev) for N in sorted({N for (_, N, _) in shapes})}
+            ws = P.new_workspace(max(max(P.fp6_linear_v2_workspace_bytes(M, N, K) for (_, N, K) in shapes), 16), dev)
+
+            def pass2():
+                for mats in stack2:
+                    for (N, K, hi, lo, sc) in mats:
+                        P.fp6_linear_v2(xs[K], hi, lo, sc, N, K, out=ys[N], workspace=ws)
+            ms = time_passes(pass2, args.steps, args.warmup)
+            layout2["M%d" % M] = ({"ms_per_step": ms, "value": 0.75 * weights_per_pass / (ms * 1e-3) / 1e9, "unit": "GB/s"}
+                                  if M <= 118 else
+                                  {"ms_per_step": ms, "value": 2.0 * M * weights_per_pass / (ms * 1e-3) / 1e12,
+                                   "unit": "TFLOP/s"})
+        del stack2
 
     # ---- fp16 dense GEMM on the same GPU, same stack (context, not the target)
     fp16 = None
@@ -352,6 +385,8 @@ def main():
     out["per_shape"] = per_shape
     if fused is not None:
         out["fused_projections"] = fused
+    if layout2 is not None:
+        out["layout2_hardware_convert"] = layout2
     if ablation is not None:
         out["bias_shift_ablation"] = ablation
     if fgq is not None:

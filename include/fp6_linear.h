@@ -240,6 +240,41 @@ int fp5_linear(const uint16_t *X, int64_t M, const void *hi_plane, const void *l
                const uint16_t *scales, int64_t N, int64_t K, uint16_t *Y,
                void *workspace, size_t workspace_bytes, void *stream, int variant, int split_k);
 
+/*
+ * FP6 in plane layout 2: the same codes, scales and sizes (N*K/2 + N*K/4 bytes), with the bits of
+ * the two planes placed so that a few logic operations merge them into the densely packed six-bit
+ * string that gfx950's packed E3M2 -> fp16 conversion (v_cvt_scalef32_pk32_f16_bf6) consumes - a
+ * hardware alternative to the bit padding of Section 5.2 that keeps the 4+2 split of Section 5.1
+ * (the 4-bit plane still holds sign and exponent bits only, the 2-bit plane mantissa bits only).
+ * Tiles, tile order, lanes and fragments are those of layout 1.  A "unit" is the 32 weights a lane
+ * holds for one 32-wide k block of a tile (kk/32 = q): element i = 8t + e, where t = nn/16 is the
+ * 16-channel fragment and e = kk%8.  Let STR be the 192-bit string with the code of element i
+ * (s eee mm) at bits 6i .. 6i+5, and STR[j] its dword j.  Bit p of STR[j] is a mantissa bit iff
+ * (32j + p) % 6 < 2.  The lane's dwords in the planes are
+ *   2-bit plane, byte offset ti*1024 + l*16 + 8q:      B0, B1
+ *   4-bit plane, byte offset ti*2048 + q*1024 + l*16:  A0, A1, A2, A3
+ * with, writing SE(j) for the sign/exponent positions of STR[j] and MA(j) for its mantissa positions,
+ *   B0 = STR[0]&MA(0) | STR[1]&MA(1) | STR[2]&MA(2)        B1 = the same of STR[3], STR[4], STR[5]
+ *   A0 = STR[0]&SE(0) | STR[4]&MA(0)
+ *   A1 = STR[1]&SE(1) | (STR[4] & 0x0C30C30C) << 2
+ *   A2 = STR[2]&SE(2) | (STR[5] & 0x030C30C3) << 2
+ *   A3 = STR[3]&SE(0) | rotate_left(STR[5] & 0xF0C30C30, 2)
+ * (SE(0) = SE(3) = 0x3CF3CF3C, SE(1) = SE(4) = 0xCF3CF3CF, SE(2) = SE(5) = 0xF3CF3CF3, MA = ~SE.)
+ * The result of the linear layer is the same up to fp32 summation order: the converted operands
+ * are the FP6 values themselves and the row scale is applied without the 2^12.  Calls mirror the
+ * layout-1 ones (row-wise scales; no tuning hints besides block_m).
+ */
+int fp6_quantize_pack_v2(const uint16_t *W, int64_t N, int64_t K, void *hi_plane, void *lo_plane,
+                         uint16_t *scales, void *stream);
+int fp6_unpack_codes_v2(const void *hi_plane, const void *lo_plane, int64_t N, int64_t K,
+                        uint8_t *codes, void *stream);
+int fp6_dequantize_v2(const void *hi_plane, const void *lo_plane, const uint16_t *scales,
+                      int64_t N, int64_t K, uint16_t *W_hat, void *stream);
+size_t fp6_linear_v2_workspace_bytes(int64_t M, int64_t N, int64_t K, int variant, int split_k);
+int fp6_linear_v2(const uint16_t *X, int64_t M, const void *hi_plane, const void *lo_plane,
+                  const uint16_t *scales, int64_t N, int64_t K, uint16_t *Y,
+                  void *workspace, size_t workspace_bytes, void *stream, int variant, int split_k);
+
 #ifdef __cplusplus
 }
 #endif

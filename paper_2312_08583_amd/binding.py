@@ -53,7 +53,9 @@ EXPORTS = ["fp6_layout_version", "fp6_status_string", "fp6_packed_sizes", "fp6_q
            "fp6_unpack_codes", "fp6_dequantize", "fp6_linear_workspace_bytes", "fp6_linear",
            "fp6_linear_variant_workspace_bytes", "fp6_linear_variant", "fp6_quantize_pack_fgq",
            "fp6_dequantize_fgq", "fp6_linear_fgq_workspace_bytes", "fp6_linear_fgq", "fp5_packed_sizes",
-           "fp5_quantize_pack", "fp5_unpack_codes", "fp5_dequantize", "fp5_linear_workspace_bytes", "fp5_linear"]
+           "fp5_quantize_pack", "fp5_unpack_codes", "fp5_dequantize", "fp5_linear_workspace_bytes", "fp5_linear",
+           "fp6_quantize_pack_v2", "fp6_unpack_codes_v2", "fp6_dequantize_v2", "fp6_linear_v2_workspace_bytes",
+           "fp6_linear_v2"]
 
 _LIB = None
 
@@ -112,6 +114,16 @@ def lib() -> ctypes.CDLL:
     L.fp5_linear_workspace_bytes.argtypes = [i64, i64, i64, ci, ci]
     L.fp5_linear.restype = ci
     L.fp5_linear.argtypes = [p, i64, p, p, p, i64, i64, p, p, sz, p, ci, ci]
+    L.fp6_quantize_pack_v2.restype = ci
+    L.fp6_quantize_pack_v2.argtypes = [p, i64, i64, p, p, p, p]
+    L.fp6_unpack_codes_v2.restype = ci
+    L.fp6_unpack_codes_v2.argtypes = [p, p, i64, i64, p, p]
+    L.fp6_dequantize_v2.restype = ci
+    L.fp6_dequantize_v2.argtypes = [p, p, p, i64, i64, p, p]
+    L.fp6_linear_v2_workspace_bytes.restype = sz
+    L.fp6_linear_v2_workspace_bytes.argtypes = [i64, i64, i64, ci, ci]
+    L.fp6_linear_v2.restype = ci
+    L.fp6_linear_v2.argtypes = [p, i64, p, p, p, i64, i64, p, p, sz, p, ci, ci]
     _LIB = L
     return L
 
@@ -337,4 +349,56 @@ def fp5_linear(X: torch.Tensor, hi: torch.Tensor, lo: torch.Tensor, scales: torc
     _check(lib().fp5_linear(xp, M, _dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"),
                             _dev(scales, torch.float16, "scales"), N, K, _dev(out, torch.float16, "Y"),
                             wp, wb, _stream(), variant, split_k), "fp5_linear")
+    return out
+
+
+# ---- FP6 in plane layout 2 (hardware conversion)
+
+def fp6_quantize_pack_v2(W: torch.Tensor):
+    wp = _dev(W, torch.float16, "W")
+    N, K = W.shape
+    hb, lb, _ = fp6_packed_sizes(N, K)
+    hi = torch.empty(hb, dtype=torch.uint8, device=W.device)
+    lo = torch.empty(lb, dtype=torch.uint8, device=W.device)
+    scales = torch.empty(N, dtype=torch.float16, device=W.device)
+    _check(lib().fp6_quantize_pack_v2(wp, N, K, hi.data_ptr(), lo.data_ptr(), scales.data_ptr(), _stream()),
+           "fp6_quantize_pack_v2")
+    return hi, lo, scales
+
+
+def fp6_unpack_codes_v2(hi: torch.Tensor, lo: torch.Tensor, N: int, K: int) -> torch.Tensor:
+    codes = torch.empty((N, K), dtype=torch.uint8, device=hi.device)
+    _check(lib().fp6_unpack_codes_v2(_dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"), N, K,
+                                     codes.data_ptr(), _stream()), "fp6_unpack_codes_v2")
+    return codes
+
+
+def fp6_dequantize_v2(hi: torch.Tensor, lo: torch.Tensor, scales: torch.Tensor, N: int, K: int) -> torch.Tensor:
+    out = torch.empty((N, K), dtype=torch.float16, device=hi.device)
+    _check(lib().fp6_dequantize_v2(_dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"),
+                                   _dev(scales, torch.float16, "scales"), N, K, out.data_ptr(), _stream()),
+           "fp6_dequantize_v2")
+    return out
+
+
+def fp6_linear_v2_workspace_bytes(M: int, N: int, K: int, variant: int = FP6_VARIANT_AUTO, split_k: int = 0) -> int:
+    return int(lib().fp6_linear_v2_workspace_bytes(M, N, K, variant, split_k))
+
+
+def fp6_linear_v2(X: torch.Tensor, hi: torch.Tensor, lo: torch.Tensor, scales: torch.Tensor, N: int, K: int,
+                  variant: int = FP6_VARIANT_AUTO, split_k: int = 0, out: Optional[torch.Tensor] = None,
+                  workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    xp = _dev(X, torch.float16, "X")
+    M = X.shape[0]
+    if X.dim() != 2 or X.shape[1] != K:
+        raise Fp6Error("X must be [M,K]")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    if workspace is None:
+        workspace = new_workspace(fp6_linear_v2_workspace_bytes(M, N, K, variant, split_k), X.device)
+    wp = workspace.data_ptr() if workspace is not None else None
+    wb = workspace.numel() if workspace is not None else 0
+    _check(lib().fp6_linear_v2(xp, M, _dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"),
+                               _dev(scales, torch.float16, "scales"), N, K, _dev(out, torch.float16, "Y"),
+                               wp, wb, _stream(), variant, split_k), "fp6_linear_v2")
     return out

@@ -72,14 +72,15 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
     // the ablations exist for the default kernel configurations only
     if (hint_dequant > 2 || (hint_dequant && (hint_waves || hint_depth))) return false;
     if (hint_half && variant != FP6_VARIANT_DECODE) return false;
-    if (hint_gbn && (variant != FP6_VARIANT_GEMM || format != kE3M2 || block || hint_dequant || hint_waves ||
+    if (hint_gbn && (variant != FP6_VARIANT_GEMM || format == kE3M1 || block || hint_dequant || hint_waves ||
                      (hint_gbn != 8 && hint_gbn != 4)))
         return false;
     // 64-channel blocks (= wavefronts) per workgroup of the tiled kernel.  Eight share the activations best;
     // four give twice the workgroups where there are few - at most 32 rows of X, or at most 32 channel blocks
     // (measured: 40 against 47 us at 32 x 28672 x 8192, 24 against 30 us at 512 x 1024 x 8192).
     const bool plain = format == kE3M2 && !block && !hint_dequant;
-    const int64_t gbn = hint_gbn ? hint_gbn : (variant == FP6_VARIANT_GEMM && plain && (M <= 32 || nblocks <= 32)) ? 4 : 8;
+    const bool narrow_ok = (plain || format == kE3M2H) && variant == FP6_VARIANT_GEMM;
+    const int64_t gbn = hint_gbn ? hint_gbn : (narrow_ok && (M <= 32 || nblocks <= 32)) ? 4 : 8;
     p.gbn = (int)gbn;
     int64_t tiles, regs_per_tile;
     if (variant == FP6_VARIANT_DECODE) {
@@ -340,6 +341,43 @@ int fp6_linear_fgq(const uint16_t* X, int64_t M, const void* hi_plane, const voi
 {
     if (block <= 0) return FP6_ERR_SHAPE;
     return linear_any(kE3M2, X, M, hi_plane, lo_plane, scales, N, K, block, Y, workspace, workspace_bytes, stream, variant,
+                      split_k);
+}
+
+// ---- FP6 in plane layout 2 (planes that merge into the operand of the hardware conversion)
+
+int fp6_quantize_pack_v2(const uint16_t* W, int64_t N, int64_t K, void* hi_plane, void* lo_plane, uint16_t* scales,
+                         void* stream)
+{
+    return quantize_pack_any(kE3M2H, W, N, K, 0, hi_plane, lo_plane, scales, stream);
+}
+
+int fp6_unpack_codes_v2(const void* hi_plane, const void* lo_plane, int64_t N, int64_t K, uint8_t* codes, void* stream)
+{
+    if (!hi_plane || !lo_plane || !codes) return FP6_ERR_NULL;
+    if (!shape_ok(N, K)) return FP6_ERR_SHAPE;
+    if (!aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(codes)) return FP6_ERR_ALIGN;
+    return launch_unpack_codes(kE3M2H, hi_plane, lo_plane, N, K, codes, (hipStream_t)stream) == hipSuccess
+               ? FP6_OK
+               : FP6_ERR_HIP;
+}
+
+int fp6_dequantize_v2(const void* hi_plane, const void* lo_plane, const uint16_t* scales, int64_t N, int64_t K,
+                      uint16_t* W_hat, void* stream)
+{
+    return dequantize_any(kE3M2H, hi_plane, lo_plane, scales, N, K, 0, W_hat, stream);
+}
+
+size_t fp6_linear_v2_workspace_bytes(int64_t M, int64_t N, int64_t K, int variant, int split_k)
+{
+    return workspace_any(kE3M2H, M, N, K, 0, variant, split_k);
+}
+
+int fp6_linear_v2(const uint16_t* X, int64_t M, const void* hi_plane, const void* lo_plane, const uint16_t* scales,
+                  int64_t N, int64_t K, uint16_t* Y, void* workspace, size_t workspace_bytes, void* stream, int variant,
+                  int split_k)
+{
+    return linear_any(kE3M2H, X, M, hi_plane, lo_plane, scales, N, K, 0, Y, workspace, workspace_bytes, stream, variant,
                       split_k);
 }
 

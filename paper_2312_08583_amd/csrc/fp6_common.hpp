@@ -24,7 +24,7 @@ constexpr int kHiTileVec = kHiTileBytes / 16;   // uint4 per tile
 constexpr int kLoTileVec = kLoTileBytes / 16;
 constexpr int kLo1TileBytes = 512;    // 1-bit plane bytes per tile (FP5): 8 bytes per lane
 template <int FMT>
-constexpr int kLoBytesOf = FMT == kE3M2 ? kLoTileBytes : kLo1TileBytes;
+constexpr int kLoBytesOf = FMT == kE3M1 ? kLo1TileBytes : kLoTileBytes;
 
 // bitwise select: mask bit 1 -> a, mask bit 0 -> b   (one v_bitop3_b32)
 __device__ __forceinline__ uint32_t bit_select(uint32_t a, uint32_t b, uint32_t mask)
@@ -50,7 +50,7 @@ __device__ __forceinline__ TileRaw load_tile(const u32x4* __restrict__ hi, const
     const u32x4* h = hi + tile_index * kHiTileVec + lane;
     r.hi0 = __builtin_nontemporal_load(h);
     r.hi1 = __builtin_nontemporal_load(h + 64);
-    if (FMT == kE3M2) {
+    if (FMT != kE3M1) {
         r.lo = __builtin_nontemporal_load(lo + tile_index * kLoTileVec + lane);
     } else {
         const u32x2 l = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(lo) + tile_index * 64 + lane);
@@ -150,10 +150,58 @@ __device__ __forceinline__ half8 unpack_tile_fragment(const TileRaw& r, int f)
     return unpack_fragment<DQ>(tile_hi_dword(r, f), tile_lo_dword(r, f) >> (4 * (f & 1)));
 }
 
+// ---- plane layout 2 (kE3M2H): merge in registers, convert in hardware ---------------------------
+// A unit = the 32 weights a lane holds for one 32-wide k block of a tile: element i = 8t + e is
+// element e (k = 8 * (lane/16) + e inside the block) of the 16-channel fragment t.  Written as a
+// string of 192 bits, code i (s eee mm) sits at bits 6i .. 6i+5: that is the operand of
+// v_cvt_scalef32_pk32_f16_bf6, which returns the 32 fp16 values - the four MFMA operands of the
+// unit - exactly (probed on the GPU for every code; the scale operand contributes its exponent).
+// The planes hold that string split by kind of bit.  Bit p of string dword j is a mantissa bit if
+// (32j + p) % 6 < 2, else a sign/exponent bit.  The unit's two dwords of the 2-bit plane are the
+// mantissa bits of string dwords 0..2 and 3..5, each at its own position (the three position sets
+// are disjoint and fill a dword).  Its four dwords of the 4-bit plane are the sign/exponent bits of
+// string dwords 0..3 at their own positions; the positions left over in them carry the
+// sign/exponent bits of string dwords 4 and 5, which a shift by two puts in place.  Merging the
+// planes back costs 11 logic operations per 32 weights.
+typedef uint32_t u32x6 __attribute__((ext_vector_type(6)));
+typedef _Float16 half32 __attribute__((ext_vector_type(32)));
+
+constexpr uint32_t kSE0 = 0x3CF3CF3Cu, kSE1 = 0xCF3CF3CFu, kSE2 = 0xF3CF3CF3u;   // sign/exponent positions of string dwords j % 3 = 0, 1, 2
+constexpr uint32_t kFromA3 = 0xF0C30C30u;   // positions of string dword 5 that come from plane dword 3 (rotated)
+
+__device__ __forceinline__ u32x6 merge_unit(u32x4 A, uint32_t B0, uint32_t B1)
+{
+    u32x6 T;
+    T[0] = bit_select(A[0], B0, kSE0);
+    T[1] = bit_select(A[1], B0, kSE1);
+    T[2] = bit_select(A[2], B0, kSE2);
+    T[3] = bit_select(A[3], B1, kSE0);
+    T[4] = bit_select(bit_select(A[0], A[1] >> 2, ~kSE0), B1, kSE1);
+    T[5] = bit_select(bit_select(__builtin_amdgcn_alignbit(A[3], A[3], 2), A[2] >> 2, kFromA3), B1, kSE2);
+    return T;
+}
+
+// The four MFMA operands (fragments t = 0..3) of k block q of a tile.
+template <int DQ, int FMT>
+__device__ __forceinline__ void unpack_kblock(const TileRaw& r, int q, half8 (&w)[4])
+{
+    if (FMT == kE3M2H) {
+        const u32x6 T = merge_unit(q ? r.hi1 : r.hi0, r.lo[2 * q], r.lo[2 * q + 1]);
+        const half32 h = __builtin_amdgcn_cvt_scalef32_pk32_f16_bf6(T, 1.0f);
+#pragma unroll
+        for (int t = 0; t < 4; t++)
+#pragma unroll
+            for (int e = 0; e < 8; e++) w[t][e] = h[8 * t + e];
+    } else {
+#pragma unroll
+        for (int t = 0; t < 4; t++) w[t] = unpack_tile_fragment<DQ, FMT>(r, 2 * t + q);
+    }
+}
+
 // What the accumulated sum has to be multiplied by besides the row scale: the 2^12 that the
 // bias shift took out of every weight (Section 5.2, Eq. 5), or nothing.
-template <int DQ>
-constexpr float kUnshift = DQ == kBiasShift ? 4096.0f : 1.0f;
+template <int DQ, int FMT = kE3M2>
+constexpr float kUnshift = (DQ == kBiasShift && FMT != kE3M2H) ? 4096.0f : 1.0f;
 
 // D(16x16, fp32) += A(16x32 fp16) * B(32x16 fp16).  Lane l supplies row l%16 of A and
 // column l%16 of B for the eight k values of group l/16, and holds D[4*(l/16)+r][l%16].

@@ -163,7 +163,7 @@ __global__ __launch_bounds__(GBN / WN * 64) void gemm_kernel(
             dma16(hb + 1024, wlane, sb + wlds + c * kWaveTileBytes + 1024);
             // FP5: the 1-bit plane has 512 bytes per tile; the upper lanes fetch them a second time
             // (into the unused half of the stage's 1 KB) rather than bytes of the next tile
-            dma16(lb, FMT == kE3M2 ? wlane : (wlane & 511u), sb + wlds + c * kWaveTileBytes + 2048);
+            dma16(lb, FMT != kE3M1 ? wlane : (wlane & 511u), sb + wlds + c * kWaveTileBytes + 2048);
         }
         if (FGQ) {
             // scales of this tile's block for the wavefront's 64 channels: 128 bytes, fetched by lanes
@@ -205,7 +205,7 @@ __global__ __launch_bounds__(GBN / WN * 64) void gemm_kernel(
         for (int c = 0; c < WN; c++) {
             raw[c].hi0 = *reinterpret_cast<const u32x4*>(wt + c * kWaveTileBytes + wlane);
             raw[c].hi1 = *reinterpret_cast<const u32x4*>(wt + c * kWaveTileBytes + 1024 + wlane);
-            if (FMT == kE3M2) {
+            if (FMT != kE3M1) {
                 raw[c].lo = *reinterpret_cast<const u32x4*>(wt + c * kWaveTileBytes + 2048 + wlane);
             } else {
                 const u32x2 l = *reinterpret_cast<const u32x2*>(wt + c * kWaveTileBytes + 2048 + lane * 8);
@@ -220,12 +220,18 @@ __global__ __launch_bounds__(GBN / WN * 64) void gemm_kernel(
                 xf[a] = *reinterpret_cast<const half8*>(st + a * 16 * (kTile * 2) + (q ? xoff1 : xoff0));
             }
 #pragma unroll
-            for (int t = 0; t < NT; t++) {
-                half8 w = unpack_tile_fragment<DQ, FMT>(raw[t / 4], 2 * (t % 4) + q);
+            for (int c = 0; c < WN; c++) {
+                half8 w4[4];
+                if (FMT == kE3M2H) unpack_kblock<DQ, FMT>(raw[c], q, w4);     // all four fragments at once
 #pragma unroll
-                for (int a = 0; a < MT; a++) {
-                    if (FGQ) part[a][t] = mfma16x16x32(w, xf[a], part[a][t]);
-                    else acc[a][t] = mfma16x16x32(w, xf[a], acc[a][t]);
+                for (int t4 = 0; t4 < 4; t4++) {
+                    const int t = 4 * c + t4;
+                    half8 w = FMT == kE3M2H ? w4[t4] : unpack_tile_fragment<DQ, FMT>(raw[c], 2 * t4 + q);
+#pragma unroll
+                    for (int a = 0; a < MT; a++) {
+                        if (FGQ) part[a][t] = mfma16x16x32(w, xf[a], part[a][t]);
+                        else acc[a][t] = mfma16x16x32(w, xf[a], acc[a][t]);
+                    }
                 }
             }
         }
@@ -332,7 +338,7 @@ __global__ __launch_bounds__(GBN / WN * 64) void gemm_kernel(
             half4 h = half4{1, 1, 1, 1};       // fine-grained scales were applied block by block
             if (!FGQ) h = *reinterpret_cast<const half4*>(scales + (size_t)nb * kTile + t * 16 + g2 * 4);
 #pragma unroll
-            for (int r = 0; r < 4; r++) sc[t][r] = (float)h[r] * kUnshift<DQ>;
+            for (int r = 0; r < 4; r++) sc[t][r] = (float)h[r] * kUnshift<DQ, FMT>;
         }
 #pragma unroll
         for (int a = 0; a < MT; a++) {

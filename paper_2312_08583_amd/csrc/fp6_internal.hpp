@@ -9,7 +9,9 @@ namespace fp6 {
 
 // Weight formats.  kE3M2: FP6, planes of 4 + 2 bits (Section 5.1).  kE3M1: FP5, the same
 // sign/exponent plane plus a 1-bit mantissa plane ("4+1"; Section 4, Section 6).
-enum Format { kE3M2 = 6, kE3M1 = 5 };
+// kE3M2H: FP6 again, with the bits of the two planes placed so that they merge into the densely packed
+// six-bit string that gfx950's packed E3M2 -> fp16 conversion instruction consumes (plane layout 2).
+enum Format { kE3M2 = 6, kE3M1 = 5, kE3M2H = 7 };
 
 // Workspace layout: [arrival counters: kCounterBytes][meeting slots: kSlotBytes][fp32 partial sums].
 // The first two regions (kZeroBytes) are zero whenever no call is running.

@@ -90,6 +90,7 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(const uint16_t* __re
     const int i = lane & 15, g = lane >> 4;
 
     uint32_t hiw[8], low[4] = {0, 0, 0, 0};
+    uint32_t T[2][7] = {{0, 0, 0, 0, 0, 0, 0}, {0, 0, 0, 0, 0, 0, 0}};     // layout 2: the two units' bit strings (+ spill-over dword)
 #pragma unroll
     for (int f = 0; f < 8; f++) {
         const int64_t n = nb * kTile + (f >> 1) * 16 + i;
@@ -101,7 +102,15 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(const uint16_t* __re
 #pragma unroll
         for (int e = 0; e < 8; e++) {
             uint16_t wb = (uint16_t)((e & 1) ? (w2[e >> 1] >> 16) : (w2[e >> 1] & 0xFFFFu));
-            constexpr int MB = FMT == kE3M2 ? 2 : 1;
+            if (FMT == kE3M2H) {
+                // code i = 8t + e of unit q = f & 1 at bits 6i .. 6i+5 of the unit's string
+                const uint32_t c = e3m2_code<2>(wb, S);
+                const int bit = 6 * (8 * (f >> 1) + e);
+                T[f & 1][bit >> 5] |= c << (bit & 31);
+                if ((bit & 31) > 26) T[f & 1][(bit >> 5) + 1] |= c >> (32 - (bit & 31));
+                continue;
+            }
+            constexpr int MB = FMT == kE3M1 ? 1 : 2;
             uint32_t c = e3m2_code<MB>(wb, S);
             const int grp = e >> 2, j = e & 3;
             const int b = 2 * (j & 1) + (j >> 1);
@@ -111,12 +120,26 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(const uint16_t* __re
         }
         hiw[f] = h;
         if (FMT == kE3M2) low[f >> 1] |= l << (4 * (f & 1));
-        else low[f >> 2] |= l << (2 * (f & 3));
+        else if (FMT == kE3M1) low[f >> 2] |= l << (2 * (f & 3));
+    }
+    if (FMT == kE3M2H) {
+        // split each string by kind of bit (the inverse of merge_unit)
+#pragma unroll
+        for (int q = 0; q < 2; q++) {
+            const uint32_t* t = T[q];
+            low[2 * q] = (t[0] & ~kSE0) | (t[1] & ~kSE1) | (t[2] & ~kSE2);
+            low[2 * q + 1] = (t[3] & ~kSE0) | (t[4] & ~kSE1) | (t[5] & ~kSE2);
+            hiw[4 * q + 0] = (t[0] & kSE0) | (t[4] & ~kSE0);
+            hiw[4 * q + 1] = (t[1] & kSE1) | ((t[4] & 0x0C30C30Cu) << 2);
+            hiw[4 * q + 2] = (t[2] & kSE2) | ((t[5] & 0x030C30C3u) << 2);
+            const uint32_t r5 = t[5] & kFromA3;
+            hiw[4 * q + 3] = (t[3] & kSE0) | (r5 << 2) | (r5 >> 30);
+        }
     }
     uint4* hp = hi + tile * kHiTileVec + lane;
     hp[0] = make_uint4(hiw[0], hiw[1], hiw[2], hiw[3]);
     hp[64] = make_uint4(hiw[4], hiw[5], hiw[6], hiw[7]);
-    if (FMT == kE3M2) lo[tile * kLoTileVec + lane] = make_uint4(low[0], low[1], low[2], low[3]);
+    if (FMT != kE3M1) lo[tile * kLoTileVec + lane] = make_uint4(low[0], low[1], low[2], low[3]);
     else reinterpret_cast<uint2*>(lo)[tile * 64 + lane] = make_uint2(low[0], low[1]);
 }
 
@@ -141,6 +164,20 @@ __device__ __forceinline__ uint32_t fragment_lo(const TileRaw& r, int f)
     return FMT == kE3M2 ? tile_lo_dword(r, f) >> (4 * (f & 1)) : r.lo[f >> 2] >> (2 * (f & 3));
 }
 
+// code of element e of fragment f of a tile, any layout (f, e compile-time constants after unrolling)
+template <int FMT>
+__device__ __forceinline__ uint32_t tile_code(const TileRaw& r, int f, int e)
+{
+    if (FMT == kE3M2H) {
+        const int q = f & 1, bit = 6 * (8 * (f >> 1) + e);
+        const u32x6 T = merge_unit(q ? r.hi1 : r.hi0, r.lo[2 * q], r.lo[2 * q + 1]);
+        uint32_t c = T[bit >> 5] >> (bit & 31);
+        if ((bit & 31) > 26) c |= T[(bit >> 5) + 1] << (32 - (bit & 31));
+        return c & 63u;
+    }
+    return fragment_code<FMT == kE3M1 ? 1 : 2>(tile_hi_dword(r, f), fragment_lo<FMT>(r, f), e);
+}
+
 template <int FMT>
 __global__ __launch_bounds__(256) void unpack_codes_kernel(const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
                                                             int64_t N, int64_t K, uint8_t* __restrict__ codes)
@@ -152,18 +189,16 @@ __global__ __launch_bounds__(256) void unpack_codes_kernel(const u32x4* __restri
     if (tile >= (N / kTile) * ktiles) return;
     const int64_t nb = tile / ktiles, kb = tile % ktiles;
     const int i = lane & 15, g = lane >> 4;
-    constexpr int MB = FMT == kE3M2 ? 2 : 1;
     TileRaw r = load_tile<FMT>(hi, lo, (size_t)tile, lane);
 #pragma unroll
     for (int f = 0; f < 8; f++) {
         const int64_t n = nb * kTile + (f >> 1) * 16 + i;
         const int64_t k = kb * kTile + (f & 1) * 32 + g * 8;
-        const uint32_t H = tile_hi_dword(r, f), L = fragment_lo<FMT>(r, f);
         uint32_t c0 = 0, c1 = 0;
 #pragma unroll
         for (int e = 0; e < 4; e++) {
-            c0 |= fragment_code<MB>(H, L, e) << (8 * e);
-            c1 |= fragment_code<MB>(H, L, 4 + e) << (8 * e);
+            c0 |= tile_code<FMT>(r, f, e) << (8 * e);
+            c1 |= tile_code<FMT>(r, f, 4 + e) << (8 * e);
         }
         *reinterpret_cast<uint2*>(codes + n * K + k) = make_uint2(c0, c1);
     }
@@ -183,18 +218,17 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const u32x4* __restrict
     if (tile >= (N / kTile) * ktiles) return;
     const int64_t nb = tile / ktiles, kb = tile % ktiles;
     const int i = lane & 15, g = lane >> 4;
-    constexpr int MB = FMT == kE3M2 ? 2 : 1;
+    constexpr int MB = FMT == kE3M1 ? 1 : 2;
     TileRaw r = load_tile<FMT>(hi, lo, (size_t)tile, lane);
 #pragma unroll
     for (int f = 0; f < 8; f++) {
         const int64_t n = nb * kTile + (f >> 1) * 16 + i;
         const int64_t k = kb * kTile + (f & 1) * 32 + g * 8;
         const float S = (float)__builtin_bit_cast(_Float16, scales[(k / block) * N + n]);
-        const uint32_t H = tile_hi_dword(r, f), L = fragment_lo<FMT>(r, f);
         uint32_t out[4];
 #pragma unroll
         for (int e = 0; e < 8; e++) {
-            const uint32_t c = fragment_code<MB>(H, L, e);
+            const uint32_t c = tile_code<FMT>(r, f, e);
             const uint32_t ex = (c >> MB) & 7, m = (c & ((1u << MB) - 1u)) << (2 - MB);   // mantissa as quarters
             // value = m/16 (subnormal) or (4+m) * 2^(ex-5)
             float mag = ex ? (float)((4 + m) << (ex - 1)) * 0.0625f : (float)m * 0.0625f;
@@ -213,9 +247,12 @@ hipError_t launch_quantize_pack(int format, const uint16_t* W, int64_t N, int64_
                                 uint16_t* scales, hipStream_t stream)
 {
     hipLaunchKernelGGL(block_scale_kernel, dim3((unsigned)(N * (K / block))), dim3(block >= 2048 ? 256 : 64), 0, stream,
-                       W, N, K, block, format == kE3M2 ? 28.0f : 24.0f, scales);
+                       W, N, K, block, format == kE3M1 ? 24.0f : 28.0f, scales);
     if (format == kE3M2)
         hipLaunchKernelGGL(quantize_pack_kernel<kE3M2>, dim3(slot_blocks(N, K)), dim3(256), 0, stream, W, N, K, block,
+                           (const uint16_t*)scales, (uint4*)hi, (uint4*)lo);
+    else if (format == kE3M2H)
+        hipLaunchKernelGGL(quantize_pack_kernel<kE3M2H>, dim3(slot_blocks(N, K)), dim3(256), 0, stream, W, N, K, block,
                            (const uint16_t*)scales, (uint4*)hi, (uint4*)lo);
     else
         hipLaunchKernelGGL(quantize_pack_kernel<kE3M1>, dim3(slot_blocks(N, K)), dim3(256), 0, stream, W, N, K, block,
@@ -229,6 +266,9 @@ hipError_t launch_unpack_codes(int format, const void* hi, const void* lo, int64
     if (format == kE3M2)
         hipLaunchKernelGGL(unpack_codes_kernel<kE3M2>, dim3(slot_blocks(N, K)), dim3(256), 0, stream, (const u32x4*)hi,
                            (const u32x4*)lo, N, K, codes);
+    else if (format == kE3M2H)
+        hipLaunchKernelGGL(unpack_codes_kernel<kE3M2H>, dim3(slot_blocks(N, K)), dim3(256), 0, stream, (const u32x4*)hi,
+                           (const u32x4*)lo, N, K, codes);
     else
         hipLaunchKernelGGL(unpack_codes_kernel<kE3M1>, dim3(slot_blocks(N, K)), dim3(256), 0, stream, (const u32x4*)hi,
                            (const u32x4*)lo, N, K, codes);
@@ -240,6 +280,9 @@ hipError_t launch_dequantize(int format, const void* hi, const void* lo, const u
 {
     if (format == kE3M2)
         hipLaunchKernelGGL(dequantize_kernel<kE3M2>, dim3(slot_blocks(N, K)), dim3(256), 0, stream, (const u32x4*)hi,
+                           (const u32x4*)lo, scales, N, K, block, W_hat);
+    else if (format == kE3M2H)
+        hipLaunchKernelGGL(dequantize_kernel<kE3M2H>, dim3(slot_blocks(N, K)), dim3(256), 0, stream, (const u32x4*)hi,
                            (const u32x4*)lo, scales, N, K, block, W_hat);
     else
         hipLaunchKernelGGL(dequantize_kernel<kE3M1>, dim3(slot_blocks(N, K)), dim3(256), 0, stream, (const u32x4*)hi,

@@ -60,3 +60,37 @@ def pack_planes5(codes: np.ndarray):
     lo = np.zeros(N * K // 8, np.uint32)
     np.bitwise_or.at(lo, (lo_addr + 0 * c).ravel(), lo_val.ravel())
     return hi.astype(np.uint8), lo.astype(np.uint8)
+
+
+def pack_planes_v2(codes: np.ndarray):
+    """FP6 codes uint8 [N,K] -> (hi bytes, lo bytes) in plane layout 2, from the header's description:
+    per lane and 32-wide k block, the 192-bit string STR of the 32 codes, split by kind of bit."""
+    N, K = codes.shape
+    assert N % 64 == 0 and K % 64 == 0
+    F = 0xFFFFFFFF
+    SE = [sum(1 << p for p in range(32) if (32 * j + p) % 6 >= 2) for j in range(6)]
+    MA = [F ^ m for m in SE]
+    hi = np.zeros(N * K // 2 // 4, np.uint32)
+    lo = np.zeros(N * K // 4 // 4, np.uint32)
+    c = codes.reshape(N // 64, 4, 16, K // 64, 2, 4, 8).astype(np.uint64)    # nb, t, n%16, kb, q, k-group, e
+    for nb in range(N // 64):
+        for kb in range(K // 64):
+            ti = nb * (K // 64) + kb
+            for q in range(2):
+                for lane in range(64):
+                    i16, g = lane % 16, lane // 16
+                    big = 0
+                    for t in range(4):
+                        for e in range(8):
+                            big |= int(c[nb, t, i16, kb, q, g, e]) << (6 * (8 * t + e))
+                    S = [(big >> (32 * j)) & F for j in range(6)]
+                    B0 = (S[0] & MA[0]) | (S[1] & MA[1]) | (S[2] & MA[2])
+                    B1 = (S[3] & MA[3]) | (S[4] & MA[4]) | (S[5] & MA[5])
+                    A0 = (S[0] & SE[0]) | (S[4] & MA[0])
+                    A1 = (S[1] & SE[1]) | (((S[4] & 0x0C30C30C) << 2) & F)
+                    A2 = (S[2] & SE[2]) | (((S[5] & 0x030C30C3) << 2) & F)
+                    r5 = S[5] & 0xF0C30C30
+                    A3 = (S[3] & SE[0]) | ((r5 << 2) & F) | (r5 >> 30)
+                    lo[(ti * 1024 + lane * 16 + 8 * q) // 4:][:2] = [B0, B1]
+                    hi[(ti * 2048 + q * 1024 + lane * 16) // 4:][:4] = [A0, A1, A2, A3]
+    return hi.view(np.uint8), lo.view(np.uint8)

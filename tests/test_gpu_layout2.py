@@ -1,0 +1,92 @@
+"""GPU parity of the FP6 calls in plane layout 2 (planes that merge into the operand of gfx950's packed
+E3M2 -> fp16 conversion): scales, codes, planes and dequantized weights bit-exact against the oracle and
+the numpy statement of the layout; Y within 2e-3 (gpu_util.assert_y_close)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2312_08583_amd as P
+from oracle import fp6_oracle as O
+from paper_2312_08583_amd import inputs
+
+from gpu_util import assert_y_close, from_np16, to_np16
+from layout_ref import pack_planes_v2
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+B = P.binding
+
+
+def test_layout2_quantize_pack_bit_exact():
+    N, K = 128, 256
+    W = inputs.weight(N, K, seed=2500, sigma=0.02, outlier_frac=0.002, device=DEV)
+    W[3] = 0
+    W[9, :64] = -W[9, :64].abs() * 1e-4
+    hi, lo, sc = P.fp6_quantize_pack_v2(W)
+    torch.cuda.synchronize()
+    codes_o, scales_o = O.quantize(to_np16(W))
+    assert np.array_equal(to_np16(sc), scales_o)
+    assert np.array_equal(P.fp6_unpack_codes_v2(hi, lo, N, K).cpu().numpy(), codes_o)
+    hi_o, lo_o = pack_planes_v2(codes_o)
+    assert np.array_equal(hi.cpu().numpy(), hi_o) and np.array_equal(lo.cpu().numpy(), lo_o)
+    assert np.array_equal(to_np16(P.fp6_dequantize_v2(hi, lo, sc, N, K)), O.dequantize(codes_o, scales_o))
+    # same scales and codes as layout 1; the planes differ
+    hi1, lo1, sc1 = P.fp6_quantize_pack(W)
+    assert torch.equal(sc, sc1) and not torch.equal(hi, hi1)
+
+
+def test_layout2_planes_round_trip_and_keep_the_4_plus_2_split():
+    rng = np.random.default_rng(4)
+    N, K = 64, 128
+    codes = rng.integers(0, 64, (N, K), dtype=np.uint8)
+    hi, lo = pack_planes_v2(codes)
+    got = P.fp6_unpack_codes_v2(torch.from_numpy(hi).to(DEV), torch.from_numpy(lo).to(DEV), N, K).cpu().numpy()
+    assert np.array_equal(got, codes)
+    # the 2-bit plane depends on the mantissas only, the 4-bit plane on sign and exponent only (Section 5.1)
+    hi_m, lo_m = pack_planes_v2(codes & 3)
+    hi_s, lo_s = pack_planes_v2(codes & 0x3C)
+    assert not hi_m.any() and np.array_equal(lo_m, lo)
+    assert not lo_s.any() and np.array_equal(hi_s, hi)
+
+
+@pytest.mark.parametrize("variant,split", [(B.FP6_VARIANT_DECODE, 1), (B.FP6_VARIANT_DECODE, 2),
+                                           (B.FP6_VARIANT_GEMM, 1), (B.FP6_VARIANT_GEMM, 2)])
+def test_layout2_one_hot_rows_read_back_dequantized_weights_bit_exact(variant, split):
+    # through the hardware conversion: every code, FP6 subnormals and -0 included
+    N, K = 128, 256
+    rng = np.random.default_rng(14)
+    codes = rng.integers(0, 64, (N, K), dtype=np.uint8)
+    codes[:, :64] = np.arange(64, dtype=np.uint8)[None, :]
+    hi, lo = pack_planes_v2(codes)
+    scales = np.linspace(0.004, 0.05, N).astype(np.float16).view(np.uint16)
+    what = O.dequantize(codes, scales)
+    what = np.where((what & 0x7FFF) == 0, 0, what).astype(np.uint16)
+    hi_d, lo_d, sc_d = torch.from_numpy(hi).to(DEV), torch.from_numpy(lo).to(DEV), from_np16(scales)
+    ks = list(range(64)) + [100, 255, 128, 191] + list(range(64, 76))
+    for k0 in range(0, len(ks), 16):
+        cols = ks[k0:k0 + 16]
+        X = torch.zeros((len(cols), K), dtype=torch.float16, device=DEV)
+        for m, k in enumerate(cols):
+            X[m, k] = 1.0
+        if variant == B.FP6_VARIANT_GEMM:
+            X = torch.cat([X, X, X[:1]])
+        Y = to_np16(P.fp6_linear_v2(X, hi_d, lo_d, sc_d, N, K, variant, split))
+        Y = np.where((Y & 0x7FFF) == 0, 0, Y).astype(np.uint16)
+        for m, k in enumerate(cols):
+            assert np.array_equal(Y[m], what[:, k]), (m, k)
+
+
+@pytest.mark.parametrize("M,variant,split", [(1, B.FP6_VARIANT_AUTO, 0), (7, B.FP6_VARIANT_DECODE, 4),
+                                             (16, B.FP6_VARIANT_DECODE, 3), (17, B.FP6_VARIANT_GEMM, 1),
+                                             (40, B.FP6_VARIANT_GEMM, 2), (100, B.FP6_VARIANT_GEMM, 1),
+                                             (300, B.FP6_VARIANT_AUTO, 0)])
+def test_layout2_linear_vs_oracle(M, variant, split):
+    N, K = 640, 1536
+    W = inputs.weight(N, K, seed=2600, sigma=0.02, outlier_frac=0.001, device=DEV)
+    X = inputs.activation(M, K, seed=2610 + M, device=DEV)
+    hi, lo, sc = P.fp6_quantize_pack_v2(W)
+    codes_o, scales_o = O.quantize(to_np16(W))
+    Yref = O.linear(to_np16(X), codes_o, scales_o)
+    Y = P.fp6_linear_v2(X, hi, lo, sc, N, K, variant, split)
+    torch.cuda.synchronize()
+    assert_y_close(Y, Yref, (M, variant, split))
