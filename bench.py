@@ -43,6 +43,8 @@ def parse():
                     help="skip the extra leg with the planes in layout 2 (hardware E3M2 -> fp16 conversion)")
     ap.add_argument("--no-ablation", action="store_true",
                     help="skip the bias-shift ablation on the paper's kernel-table shapes")
+    ap.add_argument("--no-per-shape", action="store_true",
+                    help="skip the per-shape breakdown (a profiler run then sees only the launches of the timed legs)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates the HBM byte counters of a profiler run)")
     return ap.parse_args()
@@ -134,7 +136,7 @@ def main():
     # ---- per-shape breakdown: the same launches grouped by shape (each shape over its `layers` distinct weights,
     # so every launch is cold), to show which kernel instance sits where against its roofline
     per_shape = {}
-    for M in legs:
+    for M in ([] if args.no_per_shape else legs):
         xs = {K: inputs.activation(M, K, seed=inputs.workload_seed(WORKLOAD, 9000 + M + K), device=dev)
               for K in sorted({K for (_, _, K) in shapes})}
         need = max(P.fp6_linear_workspace_bytes(M, N, K) for (_, N, K) in shapes)
