@@ -45,6 +45,10 @@ def parse():
                     help="skip the bias-shift ablation on the paper's kernel-table shapes")
     ap.add_argument("--no-per-shape", action="store_true",
                     help="skip the per-shape breakdown (a profiler run then sees only the launches of the timed legs)")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the measured ceilings (plain read kernel, MFMA-only kernel) reported beside the nominal peaks")
+    ap.add_argument("--no-mha", action="store_true",
+                    help="skip the extra leg with full-size k,v projections (the stack without grouped-query attention)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates the HBM byte counters of a profiler run)")
     return ap.parse_args()
@@ -159,6 +163,108 @@ def main():
                 row["frac"] = round(2.0 * M * N * K / us / 1e6 / MFMA_FP16_PEAK_TFLOPS, 3)
             rows.append(row)
         per_shape["M%d" % M] = rows
+
+    # ---- measured ceilings: what kernels that do nothing else sustain on this machine, for reading the two
+    # roofline fractions against (the nominal peaks stay the denominators of `frac`).  Each figure is
+    # taken over about a second of back-to-back graph replays after half a second of the same work:
+    # the shader clock takes some hundred milliseconds to settle under a new load.
+    ceilings = None
+    if not args.no_ceilings:
+        def sustained(one_pass, warm_s=0.5, run_s=1.0):
+            one_pass()
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                one_pass()
+            t0 = time.time()
+            while time.time() - t0 < warm_s:
+                g.replay()
+                torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            n, t0 = 0, time.time()
+            e0.record()
+            while time.time() - t0 < run_s:
+                g.replay()
+                n += 1
+                torch.cuda.synchronize()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n      # ms per pass
+
+        ceilings = {}
+        # (a) plain read of the same bytes in the same launch sizes: one launch per 4-bit plane of the
+        # gate projections (90 MB each, a distinct buffer per layer, so every launch is cold)
+        gate = [mats[4][2] for mats in stack]
+        best = None
+        for wgs in (1024, 2048, 4096):
+            sink = torch.zeros(wgs * 4, dtype=torch.int32, device=dev)
+
+            def read_pass():
+                for hi in gate:
+                    P.fp6_probe_read(hi, wgs, sink)
+            ms = sustained(read_pass, 0.3, 0.5)
+            gbs = sum(h.numel() for h in gate) / (ms * 1e-3) / 1e9
+            if best is None or gbs > best[0]:
+                best = (gbs, wgs, ms * 1e3 / len(gate))
+        ceilings["plain_read_per_launch"] = {"GB/s": round(best[0], 1), "workgroups": best[1], "us_per_launch": round(best[2], 2),
+                                             "what": "read-only kernel, one launch per 90 MB buffer, cold, graph replay"}
+        big = torch.empty(1 << 31, dtype=torch.uint8, device=dev)
+        sink = torch.zeros(4096 * 4, dtype=torch.int32, device=dev)
+        big.random_(0, 256)
+        ms = sustained(lambda: P.fp6_probe_read(big, 4096, sink), 0.3, 0.5)
+        ceilings["plain_read_2GiB"] = {"GB/s": round(big.numel() / (ms * 1e-3) / 1e9, 1),
+                                       "what": "read-only kernel, one launch over 2 GiB"}
+        del big
+        # (b) MFMA-only kernel (8 wavefronts per SIMD), with pseudo-random and with zero operands: the
+        # clock the chip holds depends on the operand data
+        wgs, iters, reps = 2048, 2000, 20
+        sink = torch.zeros(wgs * 256, dtype=torch.float32, device=dev)
+        for name, rnd in (("random_operands", True), ("zero_operands", False)):
+            flop = P.fp6_probe_mfma(wgs, iters, rnd, sink) * reps
+
+            def mfma_pass():
+                for _ in range(reps):
+                    P.fp6_probe_mfma(wgs, iters, rnd, sink)
+            ms = sustained(mfma_pass)
+            ceilings["mfma_only_" + name] = {"TFLOP/s": round(flop / (ms * 1e-3) / 1e12, 1), "us_per_launch": round(ms * 1e3 / reps, 1),
+                                             "what": "v_mfma_f32_16x16x32_f16 on register operands, %d workgroups x 4 wavefronts, "
+                                                     "sustained for a second" % wgs}
+
+    # ---- extra leg: the stack without grouped-query attention (k and v projections 8192 x 8192 like q):
+    # 38.9 G weights per step; the other five projections are those of the main legs
+    mha = None
+    if not args.no_mha:
+        kv = []
+        for layer in range(layers):
+            pair = []
+            for which in (1, 2):
+                W = inputs.mha_kv_weight(WORKLOAD, which, layer=layer, device=dev)
+                pair.append((W.shape[0], W.shape[1]) + tuple(P.fp6_quantize_pack(W)))
+                del W
+            kv.append(pair)
+        mha = {"what": "k,v projections 8192x8192 (no grouped-query attention), %.2f G weights per step"
+                       % ((weights_per_pass + sum(N * K - shapes[1][1] * shapes[1][2] for p_ in kv for (N, K, *_) in p_)) / 1e9)}
+        wpp = weights_per_pass + sum(N * K - shapes[1][1] * shapes[1][2] for p_ in kv for (N, K, *_) in p_)
+        for M in legs:
+            xs = {K: inputs.activation(M, K, seed=inputs.workload_seed(WORKLOAD, 9000 + M + K), device=dev)
+                  for K in sorted({K for (_, _, K) in shapes})}
+            ys = {N: torch.empty((M, N), dtype=torch.float16, device=dev) for N in sorted({N for (_, N, _) in shapes})}
+            need = max(P.fp6_linear_workspace_bytes(M, N, K) for (_, N, K) in shapes)
+            ws = P.new_workspace(max(need, 16), dev)
+
+            def mha_pass():
+                for mats, pair in zip(stack, kv):
+                    for si, (N, K, hi, lo, sc) in enumerate(mats):
+                        if si in (1, 2):
+                            N, K, hi, lo, sc = pair[si - 1]
+                        P.fp6_linear(xs[K], hi, lo, sc, N, K, out=ys[N], workspace=ws)
+            ms = time_passes(mha_pass, max(3, args.steps // 2), args.warmup)
+            mha["M%d" % M] = ({"ms_per_step": ms, "value": 0.75 * wpp / (ms * 1e-3) / 1e9, "unit": "GB/s",
+                               "frac": 0.75 * wpp / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+                              if M <= 118 else
+                              {"ms_per_step": ms, "value": 2.0 * M * wpp / (ms * 1e-3) / 1e12, "unit": "TFLOP/s",
+                               "frac": 2.0 * M * wpp / (ms * 1e-3) / 1e12 / MFMA_FP16_PEAK_TFLOPS})
+        del kv
 
     # ---- extra leg: projections that read the same input concatenated along N, as inference engines
     # store them (q,k,v -> one [10240, 8192] weight; gate,up -> one [44032, 8192]).  Row scales are per
@@ -385,6 +491,15 @@ def main():
                                     "unit": "TFLOP/s", "frac": r["tflops"] / MFMA_FP16_PEAK_TFLOPS, "traffic": traffic.get(512),
                                     "kernel": "gemm_kernel (block_m 128), all %d launches of a step" % launches}}
     out["per_shape"] = per_shape
+    if ceilings is not None:
+        out["measured_ceilings"] = ceilings
+        rd = ceilings["plain_read_per_launch"]["GB/s"]
+        mf = ceilings["mfma_only_random_operands"]["TFLOP/s"]
+        for rf in [out["roofline"]] + ([out["m512"]["roofline"]] if "m512" in out else []):
+            rf["measured_ceiling"] = rd if rf["bound"] == "hbm" else mf
+            rf["frac_of_measured_ceiling"] = rf["achieved"] / rf["measured_ceiling"]
+    if mha is not None:
+        out["mha_variant"] = mha
     if fused is not None:
         out["fused_projections"] = fused
     if layout2 is not None:

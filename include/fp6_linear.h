@@ -275,6 +275,27 @@ int fp6_linear_v2(const uint16_t *X, int64_t M, const void *hi_plane, const void
                   const uint16_t *scales, int64_t N, int64_t K, uint16_t *Y,
                   void *workspace, size_t workspace_bytes, void *stream, int variant, int split_k);
 
+/*
+ * Measurement aids (no passage of the paper: they measure the chip, not the method).  Each
+ * launches one kernel on `stream` and returns at once, like the calls above.
+ *   fp6_probe_read: `workgroups` workgroups of 256 lanes stream `bytes` (rounded down to 16) from
+ *     `buf` (device, 16-byte aligned) with 128-bit non-temporal loads; `sink` (device, at least
+ *     16 * workgroups bytes) receives one folded word per wavefront.  bytes / duration is the read
+ *     rate a kernel that does nothing else reaches on this chip.
+ *   fp6_probe_mfma: `workgroups` workgroups of 4 wavefronts; each wavefront issues 8 * iters
+ *     v_mfma_f32_16x16x32_f16 (wide == 0) or v_mfma_f32_32x32x16_f16 (wide != 0) on 8 independent
+ *     accumulators; 4 + 2 operand fragments held in registers, pseudo-random fp16 in (-1, 1) if
+ *     random_operands != 0, else zeros.  `sink` (device, at least 1024 * workgroups bytes)
+ *     receives one float per lane.  Work of a launch: workgroups * 4 * 8 * iters * 16384 flop,
+ *     twice that if wide.
+ * Errors: FP6_ERR_NULL, FP6_ERR_ALIGN, FP6_ERR_SHAPE (sizes out of range: workgroups 1 .. 2^20,
+ * iters 1 .. 2^24, bytes >= 16), FP6_ERR_WORKSPACE (sink too small), FP6_ERR_HIP.
+ */
+int fp6_probe_read(const void *buf, size_t bytes, int workgroups, void *sink, size_t sink_bytes,
+                   void *stream);
+int fp6_probe_mfma(int workgroups, int iters, int random_operands, int wide, void *sink,
+                   size_t sink_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -55,7 +55,7 @@ EXPORTS = ["fp6_layout_version", "fp6_status_string", "fp6_packed_sizes", "fp6_q
            "fp6_dequantize_fgq", "fp6_linear_fgq_workspace_bytes", "fp6_linear_fgq", "fp5_packed_sizes",
            "fp5_quantize_pack", "fp5_unpack_codes", "fp5_dequantize", "fp5_linear_workspace_bytes", "fp5_linear",
            "fp6_quantize_pack_v2", "fp6_unpack_codes_v2", "fp6_dequantize_v2", "fp6_linear_v2_workspace_bytes",
-           "fp6_linear_v2"]
+           "fp6_linear_v2", "fp6_probe_read", "fp6_probe_mfma"]
 
 _LIB = None
 
@@ -124,6 +124,10 @@ def lib() -> ctypes.CDLL:
     L.fp6_linear_v2_workspace_bytes.argtypes = [i64, i64, i64, ci, ci]
     L.fp6_linear_v2.restype = ci
     L.fp6_linear_v2.argtypes = [p, i64, p, p, p, i64, i64, p, p, sz, p, ci, ci]
+    L.fp6_probe_read.restype = ci
+    L.fp6_probe_read.argtypes = [p, sz, ci, p, sz, p]
+    L.fp6_probe_mfma.restype = ci
+    L.fp6_probe_mfma.argtypes = [ci, ci, ci, ci, p, sz, p]
     _LIB = L
     return L
 
@@ -402,3 +406,20 @@ def fp6_linear_v2(X: torch.Tensor, hi: torch.Tensor, lo: torch.Tensor, scales: t
                                _dev(scales, torch.float16, "scales"), N, K, _dev(out, torch.float16, "Y"),
                                wp, wb, _stream(), variant, split_k), "fp6_linear_v2")
     return out
+
+
+def fp6_probe_read(buf: torch.Tensor, workgroups: int, sink: torch.Tensor) -> None:
+    """One launch of the plain read kernel over all bytes of `buf` (a contiguous device tensor)."""
+    if not (buf.is_cuda and buf.is_contiguous() and sink.is_cuda and sink.is_contiguous()):
+        raise Fp6Error("buf and sink must be contiguous device tensors")
+    _check(lib().fp6_probe_read(buf.data_ptr(), buf.numel() * buf.element_size(), workgroups, sink.data_ptr(),
+                                sink.numel() * sink.element_size(), _stream()), "fp6_probe_read")
+
+
+def fp6_probe_mfma(workgroups: int, iters: int, random_operands: bool, sink: torch.Tensor, wide: bool = False) -> int:
+    """One launch of the MFMA-only kernel; returns the flop count of the launch."""
+    if not (sink.is_cuda and sink.is_contiguous()):
+        raise Fp6Error("sink must be a contiguous device tensor")
+    _check(lib().fp6_probe_mfma(workgroups, iters, int(bool(random_operands)), int(bool(wide)), sink.data_ptr(),
+                                sink.numel() * sink.element_size(), _stream()), "fp6_probe_mfma")
+    return workgroups * 4 * 8 * iters * 16384 * (2 if wide else 1)

@@ -76,3 +76,12 @@ def workload_weight(workload: str, shape_index: int, layer: int = 0, device="cpu
     seed = workload_seed(workload, 16 * layer + shape_index)
     w = weight(N, K, seed, cfg["sigma"], cfg["outlier_frac"], 10.0, device)
     return w if rows is None else w[rows[0]:rows[1]].contiguous()
+
+
+def mha_kv_weight(workload: str, which: int, layer: int = 0, device="cpu") -> torch.Tensor:
+    """k (which = 1) or v (which = 2) projection of a stack workload without grouped-query attention:
+    the shape of its q projection, same distribution, a seed of its own (slots 9 and 10 of the layer)."""
+    cfg = WORKLOADS[workload]
+    _, N, K = cfg["shapes"][0]
+    seed = workload_seed(workload, 16 * layer + 8 + which)
+    return weight(N, K, seed, cfg["sigma"], cfg["outlier_frac"], 10.0, device)

@@ -386,3 +386,30 @@ def test_zero_activations_give_zeros_and_results_do_not_depend_on_stale_output()
     P.fp6_linear(torch.zeros((M, K), dtype=torch.float16, device=DEV), hi, lo, sc, N, K, out=out)
     torch.cuda.synchronize()
     assert torch.count_nonzero(out).item() == 0          # every element written, none left NaN
+
+
+def test_probe_kernels_run_and_reject_bad_arguments():
+    """The measurement aids launch, write their sinks, and refuse sinks that are too small."""
+    buf = torch.arange(1 << 20, dtype=torch.int32, device=DEV)
+    buf[12345] ^= 0x5A5A5
+    sink = torch.zeros(64 * 4, dtype=torch.int32, device=DEV)
+    P.fp6_probe_read(buf, 64, sink)
+    torch.cuda.synchronize()
+    # the fold of all words of the buffer: the xor of 0 .. 2^20 - 1 is 0, so the planted word is what is left
+    total = 0
+    for w in sink.cpu().numpy().tolist():
+        total ^= w & 0xFFFFFFFF
+    assert total == 0x5A5A5
+    with pytest.raises(P.Fp6Error):
+        P.fp6_probe_read(buf, 65, sink)
+    out = torch.full((4 * 256,), float("nan"), dtype=torch.float32, device=DEV)
+    flop = P.fp6_probe_mfma(4, 3, False, out)
+    assert flop == 4 * 4 * 8 * 3 * 16384
+    assert P.fp6_probe_mfma(4, 3, True, out, wide=True) == 2 * flop
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all()
+    P.fp6_probe_mfma(4, 3, False, out)
+    torch.cuda.synchronize()
+    assert (out == 0).all()                   # zero operands
+    with pytest.raises(P.Fp6Error):
+        P.fp6_probe_mfma(5, 3, False, out)
