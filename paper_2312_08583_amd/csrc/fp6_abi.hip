@@ -51,7 +51,11 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
         // The streaming kernel reads X once per wavefront and tile: unbeatable up to 16 rows, still ahead of the
         // tiled kernel up to 32 rows on layers of up to 64 M weights (4096 x 4096: 9.6 against 12.8 us), behind it
         // on larger ones (28672 x 8192: 48 against 40 us), where the tiled kernel's shared X tile pays.
-        const bool stream = M <= 16 || (M <= 32 && format == kE3M2 && !block && !(variant_hints) && N * K <= ((int64_t)1 << 26));
+        // Up to 64 rows it stays ahead where there are at most 96 channel blocks, too few tiles for the tiled kernel
+        // (M = 48: 13.2 against 18.1 us at 4096 x 4096, 35 against 43 us at 5120 x 13824; behind from 8192 channels on).
+        const bool plain_call = format == kE3M2 && !block && !(variant_hints);
+        const bool stream = M <= 16 || (M <= 32 && plain_call && N * K <= ((int64_t)1 << 26)) ||
+                            (M <= 64 && plain_call && nblocks <= 96 && N * K <= ((int64_t)1 << 27));
         variant = stream ? FP6_VARIANT_DECODE : FP6_VARIANT_GEMM;
     }
     if (variant != FP6_VARIANT_DECODE && variant != FP6_VARIANT_GEMM) return false;
