@@ -32,6 +32,39 @@ static int pick_decode_split(int64_t units, int64_t ktiles, int waves)
     return best;
 }
 
+// Layers with fewer than 256 channel blocks at up to 16 rows of X: the number of K-slices and the kind of
+// workgroup (64 or 32 channels) that a small cost model likes best, in microseconds, constants fitted to
+// measurements on MI355X at M = 1 (17 shapes from 1024 x 1024 to 8192 x 28672, every divisor of the k tiles up to
+// 32): a launch costs 2.5 us; the planes stream at 6.2 TB/s, but one workgroup of four wavefronts at no more than
+// 35 GB/s (29 GB/s with 32 channels), and a compute unit works through ceil(workgroups / 256) of them; two slices
+// meet for 1.3 us, more for 1.4 + 0.03 per slice.  Against always asking for 256 workgroups this takes 11008 x 4096
+// from 10.7 to 8.0 us, 5120 x 5120 from 9.2 to 6.8, 13824 x 5120 from 14.2 to 11.3, 5120 x 13824 from 15.9 to 12.8.
+static void plan_small_decode(int64_t nblocks, int64_t ktiles, int tile_bytes, int waves, int forced_split, bool may_half,
+                              bool must_half, int* split_out, bool* half_out)
+{
+    double best = 1e30;
+    *split_out = forced_split ? forced_split : 1;
+    *half_out = must_half;
+    const double bytes = (double)nblocks * (double)ktiles * tile_bytes;
+    for (int half = must_half ? 1 : 0; half <= (may_half || must_half ? 1 : 0); half++) {
+        for (int64_t d = forced_split ? forced_split : 1; d <= (forced_split ? forced_split : 32) && d <= ktiles; d++) {
+            if (ktiles % d) continue;
+            if (d > 1 && ktiles / d < 2 * waves) break;       // every wavefront keeps at least two tiles
+            const int64_t wgs = nblocks * d * (half ? 2 : 1);
+            const double rounds = (double)((wgs + 255) / 256);
+            const double stream = bytes / 6.2e6;
+            const double unit = rounds * (bytes / (double)wgs) / (half ? 29e3 : 35e3);
+            const double meet = d == 1 ? 0.0 : d == 2 ? 1.3 : 1.4 + 0.03 * (double)d;
+            const double cost = 2.5 + (stream > unit ? stream : unit) + meet;
+            if (cost < best - 1e-9) {
+                best = cost;
+                *split_out = (int)d;
+                *half_out = half != 0;
+            }
+        }
+    }
+}
+
 // fine-grained blocks: 64 * 2^j elements, dividing K
 static bool block_ok(int64_t K, int64_t block)
 {
@@ -92,15 +125,17 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
         const bool half_ok = format == kE3M2 && !block && !hint_dequant && (!hint_waves || hint_waves == 4) &&
                              2 * nblocks <= kMaxCounters;
         if (hint_half > 2 || (hint_half == 1 && !half_ok)) return false;
-        // Measured at M <= 4: half-tile workgroups win where they give one workgroup per compute unit with
-        // no K-split or a two-way one (8192 or 4096 channels: 10.3 against 11.6 us at 8192 x 8192) - the
-        // result then needs no meeting, or a cheap one; with more workgroups per unit they lose.
-        int half_split = 0;
-        if (half_ok && M <= 4 && !hint_depth) {
-            if (2 * nblocks >= 256 && 2 * nblocks <= 288) half_split = 1;
-            else if (4 * nblocks >= 256 && 4 * nblocks <= 288 && ktiles % 2 == 0 && ktiles / 2 >= 8) half_split = 2;
+        // Measured at M <= 4: half-tile workgroups win where they give about one workgroup per compute unit with
+        // no K-split or a two-way one (10.3 against 11.6 us at 8192 x 8192); with more workgroups per unit they lose.
+        int model_split = 0;
+        bool model_half = false;
+        const int waves_now = hint_waves ? hint_waves : 4;
+        if (M <= 16 && nblocks < 256 && !hint_depth && waves_now == 4 && ktiles >= 8) {
+            const bool may_half = half_ok && M <= 4 && hint_half != 2;
+            plan_small_decode(nblocks, ktiles, format == kE3M1 ? 2560 : 3072, waves_now, split_k, may_half,
+                              hint_half == 1, &model_split, &model_half);
         }
-        p.half_tiles = hint_half == 1 || (hint_half == 0 && half_split && (!split_k || split_k == half_split));
+        p.half_tiles = hint_half == 1 || (hint_half == 0 && model_half);
         if ((hint_waves && hint_waves != 4 && hint_waves != 8) || hint_bm || hint_meet > 2 ||
             (hint_depth && !(p.half_tiles ? (hint_depth == 4 || hint_depth == 6 || hint_depth == 8)
                                           : (hint_depth >= 2 && hint_depth <= 4))))
@@ -113,8 +148,7 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
         tiles = nblocks;
         regs_per_tile = 16 * p.block_m;            // float4 per output tile (64 channels x block_m rows, fp32)
         p.split_k = split_k ? split_k
-                    : (p.half_tiles && half_split) ? half_split
-                    : (p.half_tiles && 2 * nblocks >= 256) ? 1
+                    : (model_split && M <= 16) ? model_split
                     : pick_decode_split(p.half_tiles ? 2 * nblocks : nblocks, ktiles, p.waves);
         if (block) {
             // the scales of a workgroup's K-slice are staged in LDS, 128 bytes per block of K: keep that under 96 KB
