@@ -84,11 +84,11 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
         // The streaming kernel reads X once per wavefront and tile: unbeatable up to 16 rows, still ahead of the
         // tiled kernel up to 32 rows on layers of up to 64 M weights (4096 x 4096: 9.6 against 12.8 us), behind it
         // on larger ones (28672 x 8192: 48 against 40 us), where the tiled kernel's shared X tile pays.
-        // Up to 64 rows it stays ahead where there are at most 96 channel blocks, too few tiles for the tiled kernel
-        // (M = 48: 13.2 against 18.1 us at 4096 x 4096, 35 against 43 us at 5120 x 13824; behind from 8192 channels on).
+        // Up to 64 rows it stays ahead where there are at most 64 channel blocks, too few tiles for the tiled kernel
+        // (M = 64: 15.4 against 16.2 us at 4096 x 4096, 23.3 against 27.0 at 4096 x 11008; behind from 5120 channels on).
         const bool plain_call = format == kE3M2 && !block && !(variant_hints);
         const bool stream = M <= 16 || (M <= 32 && plain_call && N * K <= ((int64_t)1 << 26)) ||
-                            (M <= 64 && plain_call && nblocks <= 96 && N * K <= ((int64_t)1 << 27));
+                            (M <= 64 && plain_call && nblocks <= 64 && N * K <= ((int64_t)1 << 27));
         variant = stream ? FP6_VARIANT_DECODE : FP6_VARIANT_GEMM;
     }
     if (variant != FP6_VARIANT_DECODE && variant != FP6_VARIANT_GEMM) return false;
@@ -113,11 +113,11 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
                      (hint_gbn != 8 && hint_gbn != 4)))
         return false;
     // 64-channel blocks (= wavefronts) per workgroup of the tiled kernel.  Eight share the activations best;
-    // four give twice the workgroups where there are few - at most 32 rows of X, or at most 32 channel blocks
-    // (measured: 40 against 47 us at 32 x 28672 x 8192, 24 against 30 us at 512 x 1024 x 8192).
+    // four give twice the workgroups where there are few (measured: 40 against 47 us at 32 x 28672 x 8192, 24
+    // against 30 us at 512 x 1024 x 8192, 20.7 against 30 us at 128 x 5120 x 5120).  The cost model below chooses.
     const bool plain = format == kE3M2 && !block && !hint_dequant;
     const bool narrow_ok = (plain || format == kE3M2H) && variant == FP6_VARIANT_GEMM;
-    const int64_t gbn = hint_gbn ? hint_gbn : (narrow_ok && (M <= 32 || nblocks <= 32)) ? 4 : 8;
+    int64_t gbn = hint_gbn ? hint_gbn : 8;
     p.gbn = (int)gbn;
     int64_t tiles, regs_per_tile;
     if (variant == FP6_VARIANT_DECODE) {
@@ -167,34 +167,43 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
             return false;
         if (M * K * 2 >= ((int64_t)1 << 32)) return false;   // X is addressed with 32-bit lane offsets
         p.waves = hint_waves ? hint_waves : 8;
-        // Pick rows per workgroup and the number of K-slices with a small cost model (microseconds,
-        // constants measured on MI355X): one workgroup per compute unit is resident, so the launch
-        // runs in ceil(workgroups/256) rounds; a round costs its k tiles at the per-tile time of the
-        // block size (or of the HBM stream, whichever is longer) plus a fixed part that grows with
-        // the number of slices the last workgroup of a tile has to add up.
+        // Pick rows per workgroup, workgroup width and the number of K-slices with a small cost model
+        // (microseconds; constants fitted on MI355X to a sweep of every plan on 12 shapes from 4096 x 4096 to
+        // 8192 x 28672 at M = 32 ... 512: the model's choice is 0.6 % behind the best plan on average, 9 % at
+        // worst).  One workgroup per compute unit is resident, and the (weight block, K-slice) pairs are dealt to
+        // the eight dies of 32 units each, so the launch takes ceil(pairs per die x row blocks / 32) rounds;
+        // a round costs its k tiles at the per-tile time of the workgroup shape (or of the HBM stream, whichever
+        // is longer) plus a fixed part that grows with the number of slices the last workgroup of a tile adds up.
         double best_cost = 0.0;
         if (block && hint_bm > 64) return false;        // fine-grained scales: two accumulators per tile
-        for (int bm = 32; bm <= (block ? 64 : 128); bm *= 2) {
-            if (hint_bm ? bm != hint_bm : (bm > 32 && bm / 2 >= M)) continue;
-            const int64_t mblk = (M + bm - 1) / bm, t = mblk * ((nblocks + gbn - 1) / gbn);
-            // (per-tile times and per-slice exchange costs of eight-wavefront workgroups; narrower ones scale)
-            const double step = (bm == 128 ? 1.47 : (bm == 64 ? 1.0 : 0.8)) * (gbn == 8 ? 1.0 : 0.55 * (double)gbn / 4.0);
-            const double slice = (bm == 128 ? 8.0 : (bm == 64 ? 2.5 : 1.5)) * (double)gbn / 8.0;
-            for (int64_t d = 1; d <= ktiles && d <= 64; d++) {
-                if (ktiles % d || (split_k && d != split_k)) continue;
-                if (d > 1 && t > kMaxCounters) break;
-                const int64_t wgs = t * d, rounds = (wgs + 255) / 256, resident = wgs < 256 ? wgs : 256;
-                const double hbm_step = 3072.0 * (double)gbn * (double)resident / (double)mblk / 5.5e6;
-                const double cost = (double)rounds * ((double)(ktiles / d) * (step > hbm_step ? step : hbm_step) + 6.0 +
-                                                      (d > 1 ? 3.0 + (double)d * slice : 0.0));
-                if (best_cost == 0.0 || cost < best_cost) {
-                    best_cost = cost;
-                    p.block_m = bm;
-                    p.split_k = (int)d;
+        int64_t best_gbn = gbn;
+        for (int64_t g = 8; g >= 4; g -= 4) {
+            if (hint_gbn ? g != hint_gbn : (g == 4 && !narrow_ok)) continue;
+            for (int bm = 32; bm <= (block ? 64 : 128); bm *= 2) {
+                if (hint_bm ? bm != hint_bm : (bm > 32 && bm / 2 >= M)) continue;
+                const int64_t mblk = (M + bm - 1) / bm, nblk = (nblocks + g - 1) / g, t = mblk * nblk;
+                const double step = (bm == 128 ? 1.575 : (bm == 64 ? 0.95 : 0.667)) * (g == 8 ? 1.0 : 0.603);
+                const double slice = (bm == 128 ? 3.745 : (bm == 64 ? 1.372 : 0.417)) * (double)g / 8.0;
+                for (int64_t d = 1; d <= ktiles && d <= 64; d++) {
+                    if (ktiles % d || (split_k && d != split_k)) continue;
+                    if (d > 1 && t > kMaxCounters) break;
+                    const int64_t wgs = t * d, resident = wgs < 256 ? wgs : 256;
+                    const int64_t rounds = ((nblk * d + 7) / 8 * mblk + 31) / 32;
+                    const double hbm_step = 3072.0 * (double)g * (double)resident / (double)mblk / 5.12e6;
+                    const double cost = (double)rounds * ((double)(ktiles / d) * (step > hbm_step ? step : hbm_step) + 3.12 +
+                                                          (d > 1 ? 1.67 + (double)d * slice : 0.0));
+                    if (best_cost == 0.0 || cost < best_cost) {
+                        best_cost = cost;
+                        p.block_m = bm;
+                        p.split_k = (int)d;
+                        best_gbn = g;
+                    }
                 }
             }
         }
         if (best_cost == 0.0) return false;
+        gbn = best_gbn;
+        p.gbn = (int)gbn;
         p.depth = (p.block_m == 128 && gbn == 8) ? 3 : 4;
         tiles = ((M + p.block_m - 1) / p.block_m) * ((nblocks + gbn - 1) / gbn);
         regs_per_tile = (int64_t)(p.block_m / 16) * 4 * 64 * gbn;

@@ -110,24 +110,16 @@ __global__ __launch_bounds__(GBN / WN * 64) void gemm_kernel(
     // Workgroups are dealt round-robin to the eight compute dies, each with its own L2.  The
     // workgroups that read the same planes (same block of weights and K-slice, different rows of
     // X) get ids that are congruent mod 8, so they run on one die and the planes are fetched
-    // into one L2 once.  The (weight block, K-slice) pairs themselves are spread over all dies.
-    // With at least eight weight blocks it is the blocks that are dealt to the dies (all K-slices
-    // of a block on one die); with fewer, the pairs are, so that no die stays idle.
+    // into one L2 once.  It is the (weight block, K-slice) pairs that are dealt to the dies, so
+    // that every die gets the same number of them, give or take one (dealing whole blocks left
+    // two dies with twice the work at 10 blocks: 512 x 5120 x 13824 in three K-slices took 136 us, now 87).
     const int xcd = blockIdx.x & 7;
     int id = blockIdx.x >> 3;
     const int mb = id % mblk;
     id /= mblk;
-    int nbw, s;
-    if (nblk >= 8) {
-        s = id % split_k;
-        nbw = (id / split_k) * 8 + xcd;
-        if (nbw >= nblk) return;             // the grid is padded to a multiple of eight blocks
-    } else {
-        const int pair = id * 8 + xcd;
-        if (pair >= nblk * split_k) return;  // ... or of eight pairs
-        nbw = pair / split_k;
-        s = pair % split_k;
-    }
+    const int pair = id * 8 + xcd;
+    if (pair >= nblk * split_k) return;      // the grid is padded to a multiple of eight pairs
+    const int nbw = pair / split_k, s = pair % split_k;
     const int kt_per = ktiles / split_k;
     const int kt_begin = s * kt_per, kt_end = kt_begin + kt_per;
     const int m0 = mb * BM;
@@ -368,8 +360,7 @@ static hipError_t launch_gemm_t(const LinearPlan& p, const uint16_t* X, int64_t 
     uint32_t* counters = reinterpret_cast<uint32_t*>(workspace);
     float4v* partials = reinterpret_cast<float4v*>(reinterpret_cast<char*>(workspace) + kZeroBytes);
     const int64_t mblk = (M + BM - 1) / BM, nblk = (N / kTile + GBN - 1) / GBN;
-    const unsigned grid = (unsigned)(nblk >= 8 ? mblk * ((nblk + 7) / 8 * 8) * p.split_k
-                                               : mblk * ((nblk * p.split_k + 7) / 8 * 8));   // padded: see the id mapping
+    const unsigned grid = (unsigned)(mblk * ((nblk * p.split_k + 7) / 8 * 8));   // padded: see the id mapping
     hipLaunchKernelGGL((gemm_kernel<BM, D, WN, DQ, FGQ, FMT, GBN>), dim3(grid), dim3(GBN / WN * 64), 0, stream, X, (int)M,
                        (const u32x4*)hi, (const u32x4*)lo, scales, (int)N, (int)K, Y, partials, counters, p.split_k, p.gshift);
     return hipGetLastError();
