@@ -4,6 +4,8 @@
 
 #include "fp6_internal.hpp"
 
+#include <cmath>
+
 namespace fp6 {
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -39,8 +41,12 @@ static int pick_decode_split(int64_t units, int64_t ktiles, int waves)
 // 35 GB/s (29 GB/s with 32 channels), and a compute unit works through ceil(workgroups / 256) of them; two slices
 // meet for 1.3 us, more for 1.4 + 0.03 per slice.  Against always asking for 256 workgroups this takes 11008 x 4096
 // from 10.7 to 8.0 us, 5120 x 5120 from 9.2 to 6.8, 13824 x 5120 from 14.2 to 11.3, 5120 x 13824 from 15.9 to 12.8.
-static void plan_small_decode(int64_t nblocks, int64_t ktiles, int tile_bytes, int waves, int forced_split, bool may_half,
-                              bool must_half, int* split_out, bool* half_out)
+//
+// With two or four 16-row blocks of X per wavefront (M > 16; 21 shapes at M = 24, 32, 48, 64) a workgroup is slower,
+// 35 GB/s x (16 / M)^0.57, the stream reaches 3.9 TB/s, and the meeting moves M / 16 times the bytes:
+// (0.5 + 0.09 per slice) x M / 16.  Mean distance from the best split of the sweep 1.5 % (the previous rule: 7 %).
+static void plan_small_decode(int64_t M, int64_t nblocks, int64_t ktiles, int tile_bytes, int waves, int forced_split,
+                              bool may_half, bool must_half, int* split_out, bool* half_out)
 {
     double best = 1e30;
     *split_out = forced_split ? forced_split : 1;
@@ -52,9 +58,13 @@ static void plan_small_decode(int64_t nblocks, int64_t ktiles, int tile_bytes, i
             if (d > 1 && ktiles / d < 2 * waves) break;       // every wavefront keeps at least two tiles
             const int64_t wgs = nblocks * d * (half ? 2 : 1);
             const double rounds = (double)((wgs + 255) / 256);
-            const double stream = bytes / 6.2e6;
-            const double unit = rounds * (bytes / (double)wgs) / (half ? 29e3 : 35e3);
-            const double meet = d == 1 ? 0.0 : d == 2 ? 1.3 : 1.4 + 0.03 * (double)d;
+            const bool rows16 = M <= 16;
+            const double stream = bytes / (rows16 ? 6.2e6 : 3.87e6);
+            const double rate = rows16 ? (half ? 29e3 : 35e3) : 35e3 * pow(16.0 / (double)M, 0.565);
+            const double unit = rounds * (bytes / (double)wgs) / rate;
+            const double meet = d == 1 ? 0.0
+                                : rows16 ? (d == 2 ? 1.3 : 1.4 + 0.03 * (double)d)
+                                         : (0.5 + 0.093 * (double)d) * (double)M / 16.0;
             const double cost = 2.5 + (stream > unit ? stream : unit) + meet;
             if (cost < best - 1e-9) {
                 best = cost;
@@ -82,12 +92,12 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
     variant &= 0xFF;
     if (variant == FP6_VARIANT_AUTO) {
         // The streaming kernel reads X once per wavefront and tile: unbeatable up to 16 rows, still ahead of the
-        // tiled kernel up to 32 rows on layers of up to 64 M weights (4096 x 4096: 9.6 against 12.8 us), behind it
+        // tiled kernel up to 32 rows on layers of up to 72 M weights (4096 x 4096: 9.6 against 12.8 us), behind it
         // on larger ones (28672 x 8192: 48 against 40 us), where the tiled kernel's shared X tile pays.
         // Up to 64 rows it stays ahead where there are at most 64 channel blocks, too few tiles for the tiled kernel
         // (M = 64: 15.4 against 16.2 us at 4096 x 4096, 23.3 against 27.0 at 4096 x 11008; behind from 5120 channels on).
         const bool plain_call = format == kE3M2 && !block && !(variant_hints);
-        const bool stream = M <= 16 || (M <= 32 && plain_call && N * K <= ((int64_t)1 << 26)) ||
+        const bool stream = M <= 16 || (M <= 32 && plain_call && N * K <= ((int64_t)72 << 20)) ||
                             (M <= 64 && plain_call && nblocks <= 64 && N * K <= ((int64_t)1 << 27));
         variant = stream ? FP6_VARIANT_DECODE : FP6_VARIANT_GEMM;
     }
@@ -130,9 +140,9 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
         int model_split = 0;
         bool model_half = false;
         const int waves_now = hint_waves ? hint_waves : 4;
-        if (M <= 16 && nblocks < 256 && !hint_depth && waves_now == 4 && ktiles >= 8) {
+        if ((M <= 16 ? nblocks < 256 : true) && !hint_depth && waves_now == 4 && ktiles >= 8) {
             const bool may_half = half_ok && M <= 4 && hint_half != 2;
-            plan_small_decode(nblocks, ktiles, format == kE3M1 ? 2560 : 3072, waves_now, split_k, may_half,
+            plan_small_decode(M, nblocks, ktiles, format == kE3M1 ? 2560 : 3072, waves_now, split_k, may_half,
                               hint_half == 1, &model_split, &model_half);
         }
         p.half_tiles = hint_half == 1 || (hint_half == 0 && model_half);
@@ -148,7 +158,7 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
         tiles = nblocks;
         regs_per_tile = 16 * p.block_m;            // float4 per output tile (64 channels x block_m rows, fp32)
         p.split_k = split_k ? split_k
-                    : (model_split && M <= 16) ? model_split
+                    : model_split ? model_split
                     : pick_decode_split(p.half_tiles ? 2 * nblocks : nblocks, ktiles, p.waves);
         if (block) {
             // the scales of a workgroup's K-slice are staged in LDS, 128 bytes per block of K: keep that under 96 KB
