@@ -49,6 +49,8 @@ def parse():
                     help="skip the measured ceilings (plain read kernel, MFMA-only kernel) reported beside the nominal peaks")
     ap.add_argument("--no-mha", action="store_true",
                     help="skip the extra leg with full-size k,v projections (the stack without grouped-query attention)")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the table of the other benchmark configurations (1-4: every shape at every M, cold weights)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates the HBM byte counters of a profiler run)")
     return ap.parse_args()
@@ -430,6 +432,38 @@ def main():
         r = [v["fp5"] / v["row_wise"] for v in fgq["shapes"].values()]
         fgq["mean_time_ratio_fp5"] = round(sum(r) / len(r), 3)       # bytes ratio: 0.625 / 0.75 = 0.833
 
+    # ---- the other benchmark configurations (1-4): every shape at every M of the configuration, each timed
+    # over a pool of distinct packed copies of at least 1 GB in turn, so every launch reads cold weights
+    configs = None
+    if not args.no_configs:
+        configs = {}
+        for wl in ("cfg1_single", "cfg2_llama7b", "cfg3_llama13b", "cfg4_llama70b_mlp"):
+            c = inputs.WORKLOADS[wl]
+            rows = []
+            for si, (name, N, K) in enumerate(c["shapes"]):
+                W = inputs.workload_weight(wl, si, device=dev)
+                hi, lo, sc = P.fp6_quantize_pack(W)
+                del W
+                copies = max(2, min(64, int(1.0e9 / (0.75 * N * K)) + 1))
+                pool = [(hi.clone(), lo.clone(), sc.clone()) for _ in range(copies)]
+                for M in c["Ms"]:
+                    X = inputs.activation(M, K, seed=inputs.workload_seed(wl, 500 + si) + M, device=dev)
+                    Y = torch.empty((M, N), dtype=torch.float16, device=dev)
+                    ws = P.new_workspace(max(P.fp6_linear_workspace_bytes(M, N, K), 16), dev)
+
+                    def sweep():
+                        for (h, l, s_) in pool:
+                            P.fp6_linear(X, h, l, s_, N, K, out=Y, workspace=ws)
+                    us = time_passes(sweep, 5, 2) * 1e3 / copies
+                    t_hbm = 0.75 * N * K / (HBM_PEAK_GBS * 1e9) * 1e6
+                    t_mfma = 2.0 * M * N * K / (MFMA_FP16_PEAK_TFLOPS * 1e12) * 1e6
+                    rows.append({"shape": "%s %dx%d" % (name, N, K), "M": M, "us": round(us, 2),
+                                 "GB/s": round(0.75 * N * K / us / 1e3, 1), "TFLOP/s": round(2.0 * M * N * K / us / 1e6, 1),
+                                 "bound": "hbm" if t_hbm >= t_mfma else "mfma",
+                                 "frac": round(max(t_hbm, t_mfma) / us, 3)})
+                del pool
+            configs[wl] = rows
+
     # ---- CPU oracle on a bounded sample of the same workload (reported baseline)
     cpu = None
     if not args.no_cpu_baseline:
@@ -500,6 +534,8 @@ def main():
             rf["frac_of_measured_ceiling"] = rf["achieved"] / rf["measured_ceiling"]
     if mha is not None:
         out["mha_variant"] = mha
+    if configs is not None:
+        out["other_configs"] = configs
     if fused is not None:
         out["fused_projections"] = fused
     if layout2 is not None:
