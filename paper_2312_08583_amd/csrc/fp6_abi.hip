@@ -179,9 +179,10 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
         p.waves = hint_waves ? hint_waves : 8;
         // Pick rows per workgroup, workgroup width and the number of K-slices with a small cost model
         // (microseconds; constants fitted on MI355X to a sweep of every plan on 12 shapes from 4096 x 4096 to
-        // 8192 x 28672 at M = 32 ... 512: the model's choice is 0.6 % behind the best plan on average, 9 % at
-        // worst).  One workgroup per compute unit is resident, and the (weight block, K-slice) pairs are dealt to
-        // the eight dies of 32 units each, so the launch takes ceil(pairs per die x row blocks / 32) rounds;
+        // 8192 x 28672 at M = 32 ... 512: the model's choice is 1 % behind the best plan on average, 7 % at
+        // worst).  One eight-wavefront workgroup or two four-wavefront ones are resident per compute unit, and the
+        // (weight block, K-slice) pairs are dealt to the eight dies of 32 units each, so the launch takes
+        // ceil(pairs per die x row blocks / (32 or 64)) rounds;
         // a round costs its k tiles at the per-tile time of the workgroup shape (or of the HBM stream, whichever
         // is longer) plus a fixed part that grows with the number of slices the last workgroup of a tile adds up.
         double best_cost = 0.0;
@@ -192,16 +193,19 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
             for (int bm = 32; bm <= (block ? 64 : 128); bm *= 2) {
                 if (hint_bm ? bm != hint_bm : (bm > 32 && bm / 2 >= M)) continue;
                 const int64_t mblk = (M + bm - 1) / bm, nblk = (nblocks + g - 1) / g, t = mblk * nblk;
-                const double step = (bm == 128 ? 1.575 : (bm == 64 ? 0.95 : 0.667)) * (g == 8 ? 1.0 : 0.603);
-                const double slice = (bm == 128 ? 3.745 : (bm == 64 ? 1.372 : 0.417)) * (double)g / 8.0;
+                const double step1 = (bm == 128 ? 1.417 : (bm == 64 ? 0.993 : 0.77)) * (g == 8 ? 1.0 : 0.57);
+                const double slice = (bm == 128 ? 4.681 : (bm == 64 ? 1.588 : 0.528)) * (double)g / 8.0;
+                const int64_t cap = g == 4 ? 2 : 1;          // four-wavefront workgroups: two per compute unit
                 for (int64_t d = 1; d <= ktiles && d <= 64; d++) {
                     if (ktiles % d || (split_k && d != split_k)) continue;
                     if (d > 1 && t > kMaxCounters) break;
-                    const int64_t wgs = t * d, resident = wgs < 256 ? wgs : 256;
-                    const int64_t rounds = ((nblk * d + 7) / 8 * mblk + 31) / 32;
-                    const double hbm_step = 3072.0 * (double)g * (double)resident / (double)mblk / 5.12e6;
-                    const double cost = (double)rounds * ((double)(ktiles / d) * (step > hbm_step ? step : hbm_step) + 3.12 +
-                                                          (d > 1 ? 1.67 + (double)d * slice : 0.0));
+                    const int64_t wgs = t * d, resident = wgs < 256 * cap ? wgs : 256 * cap;
+                    const int64_t per_die = (nblk * d + 7) / 8 * mblk;
+                    const int64_t rounds = (per_die + 32 * cap - 1) / (32 * cap);
+                    const double step = step1 * (cap == 2 && per_die > 32 ? 1.964 : 1.0);   // two sharing a unit
+                    const double hbm_step = 3072.0 * (double)g * (double)resident / (double)mblk / 4.529e6;
+                    const double cost = (double)rounds * ((double)(ktiles / d) * (step > hbm_step ? step : hbm_step) + 2.774 +
+                                                          (d > 1 ? 3.216 + (double)d * slice : 0.0));
                     if (best_cost == 0.0 || cost < best_cost) {
                         best_cost = cost;
                         p.block_m = bm;
@@ -214,7 +218,7 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
         if (best_cost == 0.0) return false;
         gbn = best_gbn;
         p.gbn = (int)gbn;
-        p.depth = (p.block_m == 128 && gbn == 8) ? 3 : 4;
+        p.depth = gbn == 8 ? (p.block_m == 128 ? 3 : 4) : (p.block_m == 128 ? 2 : (p.block_m == 64 ? 3 : 4));
         tiles = ((M + p.block_m - 1) / p.block_m) * ((nblocks + gbn - 1) / gbn);
         regs_per_tile = (int64_t)(p.block_m / 16) * 4 * 64 * gbn;
     }

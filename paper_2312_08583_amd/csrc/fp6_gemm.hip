@@ -11,11 +11,14 @@ hipError_t launch_gemm(const LinearPlan& p, const uint16_t* X, int64_t M, const 
         return launch_gemm_variant(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     // (The kernel template also supports four wavefronts owning 128 channels each, WN = 2; that shape
     // measured slower at every block size and is not instantiated.)
+    // Four-wavefront workgroups are built so that two fit a compute unit (at most 256 registers per lane and
+    // 80 KB of LDS: a ring of 4, 3 and 2 stages at 32, 64 and 128 rows), i.e. two wavefronts per SIMD as with
+    // eight-wavefront workgroups; measured 4-10 % faster than deeper rings with one workgroup per unit.
     if (p.gbn == 4) {
         switch (p.block_m) {
             case 32: return launch_gemm_t<32, 4, 1, kBiasShift, false, kE3M2, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-            case 64: return launch_gemm_t<64, 4, 1, kBiasShift, false, kE3M2, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-            default: return launch_gemm_t<128, 4, 1, kBiasShift, false, kE3M2, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+            case 64: return launch_gemm_t<64, 3, 1, kBiasShift, false, kE3M2, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+            default: return launch_gemm_t<128, 2, 1, kBiasShift, false, kE3M2, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
         }
     }
     switch (p.block_m) {

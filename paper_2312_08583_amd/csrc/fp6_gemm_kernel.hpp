@@ -83,7 +83,7 @@ __device__ __forceinline__ void wait_vmcnt()
 // GBN = 64-wide blocks of output channels per workgroup: 8 (512 channels), or 4 for launches that would
 // otherwise have too few workgroups.
 template <int BM, int D, int WN, int DQ, bool FGQ, int FMT, int GBN>
-__global__ __launch_bounds__(GBN / WN * 64) void gemm_kernel(
+__global__ __launch_bounds__(GBN / WN * 64, GBN == 4 ? 2 : 1) void gemm_kernel(
     const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
     const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
     float4v* __restrict__ partials, uint32_t* __restrict__ counters, int split_k, int gshift)

@@ -9,8 +9,8 @@ hipError_t launch_gemm_variant(const LinearPlan& p, const uint16_t* X, int64_t M
 {
     if (p.format == kE3M2H && p.gbn == 4) {
         if (p.block_m == 32) return launch_gemm_t<32, 4, 1, kBiasShift, false, kE3M2H, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-        if (p.block_m == 64) return launch_gemm_t<64, 4, 1, kBiasShift, false, kE3M2H, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
-        return launch_gemm_t<128, 4, 1, kBiasShift, false, kE3M2H, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        if (p.block_m == 64) return launch_gemm_t<64, 3, 1, kBiasShift, false, kE3M2H, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        return launch_gemm_t<128, 2, 1, kBiasShift, false, kE3M2H, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     }
     if (p.format == kE3M2H) {
         if (p.block_m == 32) return launch_gemm_t<32, 4, 1, kBiasShift, false, kE3M2H>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
