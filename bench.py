@@ -334,6 +334,16 @@ def main():
                                   if M <= 118 else
                                   {"ms_per_step": ms, "value": 2.0 * M * weights_per_pass / (ms * 1e-3) / 1e12,
                                    "unit": "TFLOP/s"})
+            # the same planes against bf16 activations (bf16 form of the conversion, bf16 MFMA, bf16 output)
+            xb = {K: inputs.activation_bf16(M, K, seed=inputs.workload_seed(WORKLOAD, 9000 + M + K), device=dev)
+                  for K in sorted({K for (_, _, K) in shapes})}
+            yb = {N: torch.empty((M, N), dtype=torch.bfloat16, device=dev) for N in sorted({N for (_, N, _) in shapes})}
+
+            def pass2b():
+                for mats in stack2:
+                    for (N, K, hi, lo, sc) in mats:
+                        P.fp6_linear_v2_bf16(xb[K], hi, lo, sc, N, K, out=yb[N], workspace=ws)
+            layout2["M%d" % M]["bf16_activations_ms_per_step"] = time_passes(pass2b, args.steps, args.warmup)
         del stack2
 
     # ---- fp16 dense GEMM on the same GPU, same stack (context, not the target)

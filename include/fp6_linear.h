@@ -276,6 +276,19 @@ int fp6_linear_v2(const uint16_t *X, int64_t M, const void *hi_plane, const void
                   void *workspace, size_t workspace_bytes, void *stream, int variant, int split_k);
 
 /*
+ * bf16 activations (Section 2 allows FP16 or BF16 around the FP6 weights): X and Y hold bf16 bit
+ * patterns, everything else is as in fp6_linear_v2 - the planes of layout 2, fp16 row scales, fp32
+ * accumulation, the same workspace size (fp6_linear_v2_workspace_bytes) and the same plans.  The
+ * weights reach the matrix cores through the bf16 form of the hardware conversion, which is exact
+ * for every E3M2 code; Y[m][n] = bf16_RNE(S_n * sum_k X[m][k] * v(c[n][k])) up to fp32 summation
+ * order.  (Bit padding as in Section 5.2 does not carry over: padded into bf16 the weights would be
+ * scaled by 2^-124 and their products would leave the normal range of the fp32 accumulator.)
+ */
+int fp6_linear_v2_bf16(const uint16_t *X, int64_t M, const void *hi_plane, const void *lo_plane,
+                       const uint16_t *scales, int64_t N, int64_t K, uint16_t *Y,
+                       void *workspace, size_t workspace_bytes, void *stream, int variant, int split_k);
+
+/*
  * Measurement aids (no passage of the paper: they measure the chip, not the method).  Each
  * launches one kernel on `stream` and returns at once, like the calls above.
  *   fp6_probe_read: `workgroups` workgroups of 256 lanes stream `bytes` (rounded down to 16) from

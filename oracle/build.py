@@ -12,7 +12,7 @@ def build(force: bool = True) -> str:
     if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
         return LIB
     cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
-           "-o", LIB, SRC]
+           "-o", LIB, SRC, "-lm"]
     subprocess.run(cmd, check=True)
     return LIB
 

@@ -28,6 +28,11 @@
  *   linear ........... Section 5.2: for row-wise scales the scale multiplies the
  *                      finished accumulation; for fine-grained (block-k) scales it
  *                      multiplies each block's product sum before the accumulation.
+ *   bf16 activations . Section 2 names BF16 beside FP16 as the type around the FP6
+ *                      weights: fp6o_linear_bf16 is the same definition on bf16 X; the two
+ *                      conversions (pattern -> value, value -> nearest pattern, ties to
+ *                      even) use <math.h> on doubles and are pinned by the tests against the
+ *                      format's definition.
  *
  * Readings taken where the paper is silent (listed again in the design notes):
  *   - round-to-nearest ties go to the even magnitude code (IEEE default);
@@ -40,6 +45,7 @@
 #include <stdint.h>
 #include <stddef.h>
 #include <stdlib.h>
+#include <math.h>
 
 #ifdef _OPENMP
 #include <omp.h>
@@ -239,6 +245,73 @@ void fp6o_linear(const uint16_t *X, int64_t M, const uint8_t *codes, const uint1
 {
     double *Xd = (double *)malloc(sizeof(double) * (size_t)(M * K > 0 ? M * K : 1));
     for (int64_t i = 0; i < M * K; i++) Xd[i] = fp6o_half_to_double(X[i]);
+#pragma omp parallel
+    {
+        double *wrow = (double *)malloc(sizeof(double) * (size_t)(K > 0 ? K : 1));
+#pragma omp for schedule(static)
+        for (int64_t n = 0; n < N; n++) {
+            for (int64_t k = 0; k < K; k++) wrow[k] = fp6o_e3m2_value(codes[n * K + k]);
+            double S = fp6o_half_to_double(scales[n]);
+            for (int64_t m = 0; m < M; m++) {
+                double acc = 0.0;
+                const double *x = Xd + m * K;
+                for (int64_t k = 0; k < K; k++) acc += x[k] * wrow[k];
+                Y[m * N + n] = S * acc;
+            }
+        }
+        free(wrow);
+    }
+    free(Xd);
+}
+
+/* ------------------------------------------------ bf16 activations */
+
+/*
+ * bf16 (1 sign, 8 exponent, 7 mantissa bits) is the upper half of an IEEE single: the value of a
+ * bit pattern b is that of the single with bits b << 16 (Section 2 names BF16 beside FP16 as the
+ * type around the FP6 weights).
+ */
+double fp6o_bf16_to_double(uint16_t b)
+{
+    union { uint32_t u; float f; } v;
+    v.u = (uint32_t)b << 16;
+    return (double)v.f;
+}
+
+/*
+ * A double rounded to bf16, round to nearest, ties to the even mantissa; finite inputs inside the
+ * bf16 range only (the results of a linear layer).  Written out on the value, not on float bits:
+ * the spacing of bf16 numbers in the binade of x is 2^(floor(log2|x|) - 7), and subnormals
+ * (|x| < 2^-126) have spacing 2^-133.
+ */
+uint16_t fp6o_double_to_bf16(double x)
+{
+    uint16_t sign = (uint16_t)(signbit(x) ? 0x8000u : 0u);
+    double a = fabs(x);
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e);                 /* a = f * 2^e, 0.5 <= f < 1  ->  floor(log2 a) = e - 1 */
+    int ex = e - 1;
+    if (ex < -126) ex = -126;           /* subnormal range shares the spacing of the lowest binade */
+    double q = ldexp(a, 7 - ex);        /* in units of the spacing: 128 <= q < 256 for normal numbers */
+    double r = nearbyint(q);            /* the default rounding mode is to nearest, ties to even */
+    uint32_t m = (uint32_t)r;
+    uint32_t bits;
+    if (ex == -126 && m < 128u) {
+        bits = m;                       /* subnormal: exponent field 0 */
+    } else {
+        if (m == 256u) { m = 128u; ex += 1; }
+        bits = ((uint32_t)(ex + 127) << 7) | (m - 128u);
+    }
+    return (uint16_t)(sign | (uint16_t)bits);
+}
+
+/* fp6o_linear with X given as bf16 bit patterns: the same definition, Y in double. */
+void fp6o_linear_bf16(const uint16_t *X, int64_t M, const uint8_t *codes, const uint16_t *scales,
+                      int64_t N, int64_t K, double *Y)
+{
+    double *Xd = (double *)malloc(sizeof(double) * (size_t)(M * K > 0 ? M * K : 1));
+    for (int64_t i = 0; i < M * K; i++) Xd[i] = fp6o_bf16_to_double(X[i]);
 #pragma omp parallel
     {
         double *wrow = (double *)malloc(sizeof(double) * (size_t)(K > 0 ? K : 1));

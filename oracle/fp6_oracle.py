@@ -44,6 +44,12 @@ def lib() -> ctypes.CDLL:
         L.fp6o_quantize_fgq.argtypes = [p, i64, i64, i64, p, p]
         L.fp6o_dequantize_fgq.restype = None
         L.fp6o_dequantize_fgq.argtypes = [p, p, i64, i64, i64, p]
+        L.fp6o_linear_bf16.restype = None
+        L.fp6o_linear_bf16.argtypes = [p, i64, p, p, i64, i64, p]
+        L.fp6o_bf16_to_double.restype = ctypes.c_double
+        L.fp6o_bf16_to_double.argtypes = [ctypes.c_uint16]
+        L.fp6o_double_to_bf16.restype = ctypes.c_uint16
+        L.fp6o_double_to_bf16.argtypes = [ctypes.c_double]
         L.fp6o_linear_fgq.restype = None
         L.fp6o_linear_fgq.argtypes = [p, i64, p, p, i64, i64, i64, p]
         L.fp5o_e3m1_value.restype = ctypes.c_double
@@ -158,6 +164,30 @@ def linear(X, codes, scales) -> np.ndarray:
     assert K == K2 and scales.size == N
     Y = np.zeros((M, N), np.float64)
     lib().fp6o_linear(_ptr(X), M, _ptr(codes), _ptr(scales), N, K, _ptr(Y))
+    return Y
+
+
+# ---- bf16 activations (Section 2: FP16 or BF16 around the FP6 weights)
+
+def bf16_to_double(bits: int) -> float:
+    return float(lib().fp6o_bf16_to_double(int(bits) & 0xFFFF))
+
+
+def double_to_bf16(x: float) -> int:
+    """Round to nearest, ties to even; finite x inside the bf16 range."""
+    return int(lib().fp6o_double_to_bf16(float(x)))
+
+
+def linear_bf16(X, codes, scales) -> np.ndarray:
+    """X bf16 bit patterns (uint16) [M,K]; codes [N,K]; scales fp16 [N] -> Y float64 [M,N]."""
+    X = np.ascontiguousarray(X, dtype=np.uint16)
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = _bits(scales).reshape(-1)
+    M, K = X.shape
+    N, K2 = codes.shape
+    assert K == K2 and scales.size == N
+    Y = np.zeros((M, N), np.float64)
+    lib().fp6o_linear_bf16(_ptr(X), M, _ptr(codes), _ptr(scales), N, K, _ptr(Y))
     return Y
 
 

@@ -55,7 +55,7 @@ EXPORTS = ["fp6_layout_version", "fp6_status_string", "fp6_packed_sizes", "fp6_q
            "fp6_dequantize_fgq", "fp6_linear_fgq_workspace_bytes", "fp6_linear_fgq", "fp5_packed_sizes",
            "fp5_quantize_pack", "fp5_unpack_codes", "fp5_dequantize", "fp5_linear_workspace_bytes", "fp5_linear",
            "fp6_quantize_pack_v2", "fp6_unpack_codes_v2", "fp6_dequantize_v2", "fp6_linear_v2_workspace_bytes",
-           "fp6_linear_v2", "fp6_probe_read", "fp6_probe_mfma"]
+           "fp6_linear_v2", "fp6_linear_v2_bf16", "fp6_probe_read", "fp6_probe_mfma"]
 
 _LIB = None
 
@@ -124,6 +124,8 @@ def lib() -> ctypes.CDLL:
     L.fp6_linear_v2_workspace_bytes.argtypes = [i64, i64, i64, ci, ci]
     L.fp6_linear_v2.restype = ci
     L.fp6_linear_v2.argtypes = [p, i64, p, p, p, i64, i64, p, p, sz, p, ci, ci]
+    L.fp6_linear_v2_bf16.restype = ci
+    L.fp6_linear_v2_bf16.argtypes = [p, i64, p, p, p, i64, i64, p, p, sz, p, ci, ci]
     L.fp6_probe_read.restype = ci
     L.fp6_probe_read.argtypes = [p, sz, ci, p, sz, p]
     L.fp6_probe_mfma.restype = ci
@@ -423,3 +425,23 @@ def fp6_probe_mfma(workgroups: int, iters: int, random_operands: bool, sink: tor
     _check(lib().fp6_probe_mfma(workgroups, iters, int(bool(random_operands)), int(bool(wide)), sink.data_ptr(),
                                 sink.numel() * sink.element_size(), _stream()), "fp6_probe_mfma")
     return workgroups * 4 * 8 * iters * 16384 * (2 if wide else 1)
+
+
+def fp6_linear_v2_bf16(X: torch.Tensor, hi: torch.Tensor, lo: torch.Tensor, scales: torch.Tensor, N: int, K: int,
+                       variant: int = FP6_VARIANT_AUTO, split_k: int = 0, out: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Layout-2 planes against bf16 activations; returns bf16."""
+    xp = _dev(X, torch.bfloat16, "X")
+    M = X.shape[0]
+    if X.dim() != 2 or X.shape[1] != K:
+        raise Fp6Error("X must be [M,K]")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=X.device)
+    if workspace is None:
+        workspace = new_workspace(fp6_linear_v2_workspace_bytes(M, N, K, variant, split_k), X.device)
+    wp = workspace.data_ptr() if workspace is not None else None
+    wb = workspace.numel() if workspace is not None else 0
+    _check(lib().fp6_linear_v2_bf16(xp, M, _dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"),
+                                    _dev(scales, torch.float16, "scales"), N, K, _dev(out, torch.bfloat16, "Y"),
+                                    wp, wb, _stream(), variant, split_k), "fp6_linear_v2_bf16")
+    return out

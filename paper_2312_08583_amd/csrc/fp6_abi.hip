@@ -126,7 +126,7 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
     // four give twice the workgroups where there are few (measured: 40 against 47 us at 32 x 28672 x 8192, 24
     // against 30 us at 512 x 1024 x 8192, 20.7 against 30 us at 128 x 5120 x 5120).  The cost model below chooses.
     const bool plain = format == kE3M2 && !block && !hint_dequant;
-    const bool narrow_ok = (plain || format == kE3M2H) && variant == FP6_VARIANT_GEMM;
+    const bool narrow_ok = (plain || layout2(format)) && variant == FP6_VARIANT_GEMM;
     int64_t gbn = hint_gbn ? hint_gbn : 8;
     p.gbn = (int)gbn;
     int64_t tiles, regs_per_tile;
@@ -439,6 +439,14 @@ int fp6_linear_v2(const uint16_t* X, int64_t M, const void* hi_plane, const void
                   int split_k)
 {
     return linear_any(kE3M2H, X, M, hi_plane, lo_plane, scales, N, K, 0, Y, workspace, workspace_bytes, stream, variant,
+                      split_k);
+}
+
+int fp6_linear_v2_bf16(const uint16_t* X, int64_t M, const void* hi_plane, const void* lo_plane, const uint16_t* scales,
+                       int64_t N, int64_t K, uint16_t* Y, void* workspace, size_t workspace_bytes, void* stream,
+                       int variant, int split_k)
+{
+    return linear_any(kE3M2B, X, M, hi_plane, lo_plane, scales, N, K, 0, Y, workspace, workspace_bytes, stream, variant,
                       split_k);
 }
 

@@ -165,6 +165,8 @@ __device__ __forceinline__ half8 unpack_tile_fragment(const TileRaw& r, int f)
 // planes back costs 11 logic operations per 32 weights.
 typedef uint32_t u32x6 __attribute__((ext_vector_type(6)));
 typedef _Float16 half32 __attribute__((ext_vector_type(32)));
+typedef __bf16 bf16x32 __attribute__((ext_vector_type(32)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr uint32_t kSE0 = 0x3CF3CF3Cu, kSE1 = 0xCF3CF3CFu, kSE2 = 0xF3CF3CF3u;   // sign/exponent positions of string dwords j % 3 = 0, 1, 2
 constexpr uint32_t kFromA3 = 0xF0C30C30u;   // positions of string dword 5 that come from plane dword 3 (rotated)
@@ -192,6 +194,17 @@ __device__ __forceinline__ void unpack_kblock(const TileRaw& r, int q, half8 (&w
         for (int t = 0; t < 4; t++)
 #pragma unroll
             for (int e = 0; e < 8; e++) w[t][e] = h[8 * t + e];
+    } else if (FMT == kE3M2B) {
+        // bf16 operands travel in the same 128-bit registers; only the MFMA and the final conversion know
+        const u32x6 T = merge_unit(q ? r.hi1 : r.hi0, r.lo[2 * q], r.lo[2 * q + 1]);
+        const bf16x32 h = __builtin_amdgcn_cvt_scalef32_pk32_bf16_bf6(T, 1.0f);
+#pragma unroll
+        for (int t = 0; t < 4; t++) {
+            bf16x8 b;
+#pragma unroll
+            for (int e = 0; e < 8; e++) b[e] = h[8 * t + e];
+            w[t] = __builtin_bit_cast(half8, b);
+        }
     } else {
 #pragma unroll
         for (int t = 0; t < 4; t++) w[t] = unpack_tile_fragment<DQ, FMT>(r, 2 * t + q);
@@ -201,13 +214,39 @@ __device__ __forceinline__ void unpack_kblock(const TileRaw& r, int q, half8 (&w
 // What the accumulated sum has to be multiplied by besides the row scale: the 2^12 that the
 // bias shift took out of every weight (Section 5.2, Eq. 5), or nothing.
 template <int DQ, int FMT = kE3M2>
-constexpr float kUnshift = (DQ == kBiasShift && FMT != kE3M2H) ? 4096.0f : 1.0f;
+constexpr float kUnshift = (DQ == kBiasShift && !layout2(FMT)) ? 4096.0f : 1.0f;
 
 // D(16x16, fp32) += A(16x32 fp16) * B(32x16 fp16).  Lane l supplies row l%16 of A and
 // column l%16 of B for the eight k values of group l/16, and holds D[4*(l/16)+r][l%16].
 __device__ __forceinline__ float4v mfma16x16x32(half8 a, half8 b, float4v c)
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+// The same for the element type of the format: bf16 operands for kE3M2B (carried in half8 registers), fp16 otherwise.
+template <int FMT>
+__device__ __forceinline__ float4v mfma16x16x32_of(half8 a, half8 b, float4v c)
+{
+    if (FMT == kE3M2B)
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+// Four results to the 16-bit output type of the format (round to nearest even), as they are stored.
+template <int FMT>
+__device__ __forceinline__ half4 to_out4(const float (&v)[4])
+{
+    if (FMT == kE3M2B) {
+        typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+        bf16x4 y;
+#pragma unroll
+        for (int r = 0; r < 4; r++) y[r] = (__bf16)v[r];
+        return __builtin_bit_cast(half4, y);
+    }
+    half4 y;
+#pragma unroll
+    for (int r = 0; r < 4; r++) y[r] = (_Float16)v[r];
+    return y;
 }
 
 }  // namespace fp6

@@ -38,7 +38,7 @@ __device__ __forceinline__ XFrag load_x(const uint16_t* __restrict__ xrow, int k
 template <int DQ, int FMT, int MB>
 __device__ __forceinline__ void tile_mac(const TileRaw& r, const XFrag (&x)[MB], float4v (&acc)[MB][4])
 {
-    if (FMT == kE3M2H) {
+    if (layout2(FMT)) {
         // layout 2: the unpack yields the four fragments of a k block at once
 #pragma unroll
         for (int q = 0; q < 2; q++) {
@@ -47,7 +47,7 @@ __device__ __forceinline__ void tile_mac(const TileRaw& r, const XFrag (&x)[MB],
 #pragma unroll
             for (int t = 0; t < 4; t++)
 #pragma unroll
-                for (int c = 0; c < MB; c++) acc[c][t] = mfma16x16x32(w[t], q ? x[c].q1 : x[c].q0, acc[c][t]);
+                for (int c = 0; c < MB; c++) acc[c][t] = mfma16x16x32_of<FMT>(w[t], q ? x[c].q1 : x[c].q0, acc[c][t]);
         }
         return;
     }
@@ -55,7 +55,7 @@ __device__ __forceinline__ void tile_mac(const TileRaw& r, const XFrag (&x)[MB],
     for (int f = 0; f < 8; f++) {
         half8 w = unpack_tile_fragment<DQ, FMT>(r, f);
 #pragma unroll
-        for (int c = 0; c < MB; c++) acc[c][f >> 1] = mfma16x16x32(w, (f & 1) ? x[c].q1 : x[c].q0, acc[c][f >> 1]);
+        for (int c = 0; c < MB; c++) acc[c][f >> 1] = mfma16x16x32_of<FMT>(w, (f & 1) ? x[c].q1 : x[c].q0, acc[c][f >> 1]);
     }
 }
 
@@ -251,9 +251,10 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
     for (int c = 0; c < MB; c++) {
         const bool lo_ok = c ? active[c] : keep_lo, hi_ok = c ? active[c] : keep_hi;
         if (!(lo_ok || hi_ok)) continue;
-        half4 y;
+        float yv[4];
 #pragma unroll
-        for (int r = 0; r < 4; r++) y[r] = (_Float16)(sum[c][r] * ((float)sc[r] * kUnshift<DQ, FMT>));
+        for (int r = 0; r < 4; r++) yv[r] = sum[c][r] * ((float)sc[r] * kUnshift<DQ, FMT>);
+        const half4 y = to_out4<FMT>(yv);
         uint16_t* dst = Y + (size_t)(16 * c + mm) * N + nb * kTile + n4 * 4;
         if (lo_ok && hi_ok) {
             *reinterpret_cast<half4*>(dst) = y;
@@ -458,6 +459,7 @@ hipError_t launch_decode(const LinearPlan& p, const uint16_t* X, int64_t M, cons
         return launch_decode_half_t<4, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     }
     if (p.format == kE3M2H) return launch_decode_t<4, 4, kBiasShift, false, kE3M2H>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+    if (p.format == kE3M2B) return launch_decode_t<4, 4, kBiasShift, false, kE3M2B>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     if (p.format == kE3M1) return launch_decode_t<4, 4, kBiasShift, false, kE3M1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     if (p.gshift >= 0) return launch_decode_t<4, 4, kBiasShift, true>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     if (p.dequant == kIntRebias) return launch_decode_t<4, 4, kIntRebias>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);

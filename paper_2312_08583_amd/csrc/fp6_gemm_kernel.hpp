@@ -218,15 +218,15 @@ __global__ __launch_bounds__(GBN / WN * 64, GBN == 4 ? 2 : 1) void gemm_kernel(
 #pragma unroll
             for (int c = 0; c < WN; c++) {
                 half8 w4[4];
-                if (FMT == kE3M2H) unpack_kblock<DQ, FMT>(raw[c], q, w4);     // all four fragments at once
+                if (layout2(FMT)) unpack_kblock<DQ, FMT>(raw[c], q, w4);     // all four fragments at once
 #pragma unroll
                 for (int t4 = 0; t4 < 4; t4++) {
                     const int t = 4 * c + t4;
-                    half8 w = FMT == kE3M2H ? w4[t4] : unpack_tile_fragment<DQ, FMT>(raw[c], 2 * t4 + q);
+                    half8 w = layout2(FMT) ? w4[t4] : unpack_tile_fragment<DQ, FMT>(raw[c], 2 * t4 + q);
 #pragma unroll
                     for (int a = 0; a < MT; a++) {
-                        if (FGQ) part[a][t] = mfma16x16x32(w, xf[a], part[a][t]);
-                        else acc[a][t] = mfma16x16x32(w, xf[a], acc[a][t]);
+                        if (FGQ) part[a][t] = mfma16x16x32_of<FMT>(w, xf[a], part[a][t]);
+                        else acc[a][t] = mfma16x16x32_of<FMT>(w, xf[a], acc[a][t]);
                     }
                 }
             }
@@ -342,10 +342,10 @@ __global__ __launch_bounds__(GBN / WN * 64, GBN == 4 ? 2 : 1) void gemm_kernel(
             if (m < M) {
 #pragma unroll
                 for (int t = 0; t < 4; t++) {
-                    half4 y;
+                    float yv[4];
 #pragma unroll
-                    for (int r = 0; r < 4; r++) y[r] = (_Float16)(acc[a][c * 4 + t][r] * sc[t][r]);
-                    *reinterpret_cast<half4*>(Y + (size_t)m * N + (size_t)nb * kTile + t * 16 + g2 * 4) = y;
+                    for (int r = 0; r < 4; r++) yv[r] = acc[a][c * 4 + t][r] * sc[t][r];
+                    *reinterpret_cast<half4*>(Y + (size_t)m * N + (size_t)nb * kTile + t * 16 + g2 * 4) = to_out4<FMT>(yv);
                 }
             }
         }

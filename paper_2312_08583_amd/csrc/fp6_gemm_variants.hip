@@ -7,6 +7,7 @@ hipError_t launch_gemm_variant(const LinearPlan& p, const uint16_t* X, int64_t M
                                const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                                hipStream_t stream)
 {
+    if (p.format == kE3M2B) return launch_gemm_bf16(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     if (p.format == kE3M2H && p.gbn == 4) {
         if (p.block_m == 32) return launch_gemm_t<32, 4, 1, kBiasShift, false, kE3M2H, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
         if (p.block_m == 64) return launch_gemm_t<64, 3, 1, kBiasShift, false, kE3M2H, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);

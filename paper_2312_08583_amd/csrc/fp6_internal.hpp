@@ -11,7 +11,10 @@ namespace fp6 {
 // sign/exponent plane plus a 1-bit mantissa plane ("4+1"; Section 4, Section 6).
 // kE3M2H: FP6 again, with the bits of the two planes placed so that they merge into the densely packed
 // six-bit string that gfx950's packed E3M2 -> fp16 conversion instruction consumes (plane layout 2).
-enum Format { kE3M2 = 6, kE3M1 = 5, kE3M2H = 7 };
+// kE3M2B: the planes of kE3M2H with bf16 activations and bf16 output (the conversion to bf16 is the same instruction's
+//         bf16 form; plain bit padding does not carry over to bf16, whose padded values would sit at 2^-124).
+enum Format { kE3M2 = 6, kE3M1 = 5, kE3M2H = 7, kE3M2B = 8 };
+constexpr bool layout2(int format) { return format == kE3M2H || format == kE3M2B; }
 
 // Workspace layout: [arrival counters: kCounterBytes][meeting slots: kSlotBytes][fp32 partial sums].
 // The first two regions (kZeroBytes) are zero whenever no call is running.
@@ -56,6 +59,9 @@ hipError_t launch_decode(const LinearPlan& p, const uint16_t* X, int64_t M, cons
                          hipStream_t stream);
 // fp6_gemm_variants.hip: plans with an ablation unpack, fine-grained scales or the five-bit format
 hipError_t launch_gemm_variant(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
+                               const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
+                               hipStream_t stream);
+hipError_t launch_gemm_bf16(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
                                const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                                hipStream_t stream);
 hipError_t launch_gemm(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,

@@ -85,3 +85,9 @@ def mha_kv_weight(workload: str, which: int, layer: int = 0, device="cpu") -> to
     _, N, K = cfg["shapes"][0]
     seed = workload_seed(workload, 16 * layer + 8 + which)
     return weight(N, K, seed, cfg["sigma"], cfg["outlier_frac"], 10.0, device)
+
+
+def activation_bf16(M: int, K: int, seed: int, device="cpu") -> torch.Tensor:
+    """bf16 [M,K] activations ~ N(0,1) (the same draw as `activation`, rounded to bf16)."""
+    g = _gen(seed, device)
+    return torch.randn((M, K), generator=g, device=device, dtype=torch.float32).to(torch.bfloat16).contiguous()

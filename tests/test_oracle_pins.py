@@ -2,6 +2,7 @@
 paper or by mathematics (closed forms, a library's fp16 arithmetic, exact rational
 brute force, invariants) - never against the oracle's own formulas and never against
 the HIP path."""
+import math
 import os
 from fractions import Fraction
 
@@ -539,3 +540,64 @@ def test_e3m1_dequantize_and_linear_vs_numpy():
     sc = np.array([2.0 ** -k for k in range(N)], np.float16)
     Wv = vals[codes]
     assert np.array_equal(O.linear5(X, codes, sc.view(np.uint16)), (X.astype(np.float64) @ Wv.T) * sc.astype(np.float64)[None, :])
+
+
+# ---- bf16 activations (Section 2: FP16 or BF16 around the FP6 weights)
+
+def _bf16_value(bits: int) -> Fraction:
+    """bf16 bit pattern -> exact value, from the format's definition (1-8-7, bias 127)."""
+    s, e, m = bits >> 15, (bits >> 7) & 0xFF, bits & 0x7F
+    assert e != 0xFF
+    mag = Fraction(m, 128) * Fraction(2) ** (-126) if e == 0 else (1 + Fraction(m, 128)) * Fraction(2) ** (e - 127)
+    return -mag if s else mag
+
+
+def test_bf16_to_double_is_the_format_definition_for_every_finite_pattern():
+    for bits in range(0x10000):
+        if (bits >> 7) & 0xFF == 0xFF:
+            continue
+        assert Fraction(O.bf16_to_double(bits)) == _bf16_value(bits), hex(bits)
+    assert math.copysign(1.0, O.bf16_to_double(0x8000)) == -1.0
+
+
+def test_double_to_bf16_rounds_to_nearest_ties_to_even():
+    # every finite pattern is a fixed point; the midpoint to the next pattern goes to the even one;
+    # just below / above the midpoint goes down / up
+    for bits in list(range(0, 0x7F80, 7)) + [0x0001, 0x007F, 0x0080, 0x7F7E]:
+        v = _bf16_value(bits)
+        assert O.double_to_bf16(float(v)) == bits
+        assert O.double_to_bf16(-float(v)) == bits | 0x8000          # -0.0 for the zero pattern
+        if bits + 1 < 0x7F80:
+            mid = (v + _bf16_value(bits + 1)) / 2
+            even = bits if bits % 2 == 0 else bits + 1
+            assert O.double_to_bf16(float(mid)) == even, hex(bits)
+            eps = (_bf16_value(bits + 1) - v) / 1024
+            assert O.double_to_bf16(float(mid - eps)) == bits
+            assert O.double_to_bf16(float(mid + eps)) == bits + 1
+    # a library routine on values it converts without a second rounding (float32-exact inputs)
+    import torch
+    x = np.random.default_rng(31).standard_normal(5000).astype(np.float32) * np.float32(37.0)
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = np.array([O.double_to_bf16(float(v)) for v in x], dtype=np.uint16)
+    assert np.array_equal(got, want)
+
+
+def test_linear_bf16_is_linear_on_values_both_types_hold_and_bruteforce():
+    rng = np.random.default_rng(32)
+    M, N, K = 3, 4, 40
+    codes = rng.integers(0, 64, (N, K), dtype=np.uint8)
+    scales = rng.integers(0x1000, 0x3C00, N).astype(np.uint16)
+    # multiples of 1/8 up to 8: exact in fp16 and in bf16
+    Xv = rng.integers(-64, 65, (M, K)) / 8.0
+    X16 = Xv.astype(np.float16)
+    Xb = np.array([[O.double_to_bf16(float(v)) for v in row] for row in Xv], dtype=np.uint16)
+    assert np.array_equal(O.linear_bf16(Xb, codes, scales), O.linear(X16, codes, scales))
+    # arbitrary bf16 patterns (values fp16 cannot hold) against exact rational arithmetic
+    Xb = rng.integers(0x3000, 0x4800, (M, K)).astype(np.uint16) | (rng.integers(0, 2, (M, K)).astype(np.uint16) << 15)
+    Y = O.linear_bf16(Xb, codes, scales)
+    for m in range(M):
+        for n in range(N):
+            S = Fraction(float(scales[n:n + 1].view(np.float16)[0]))
+            exact = S * sum(_bf16_value(int(Xb[m, k])) * Fraction(MAGS[codes[n, k] & 31]) * (-1 if codes[n, k] & 32 else 1)
+                            for k in range(K))
+            assert abs(Y[m, n] - float(exact)) <= 1e-13 * max(1.0, abs(float(exact)))
