@@ -413,3 +413,25 @@ def test_probe_kernels_run_and_reject_bad_arguments():
     assert (out == 0).all()                   # zero operands
     with pytest.raises(P.Fp6Error):
         P.fp6_probe_mfma(5, 3, False, out)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_automatic_plans_on_random_shapes(seed):
+    """Whatever kernel, workgroup shape and K-split the planner picks: sampled channels against the oracle.
+    Shapes are log-uniform in N, K <= 8192 and M <= 700, eight per seed."""
+    import math
+    rng = np.random.default_rng(4200 + seed)
+    for i in range(8):
+        N = 64 * int(round(math.exp(rng.uniform(0.0, math.log(128)))))
+        K = 64 * int(round(math.exp(rng.uniform(0.0, math.log(128)))))
+        M = int(round(math.exp(rng.uniform(0.0, math.log(700)))))
+        W = inputs.weight(N, K, seed=4300 + 10 * seed + i, sigma=0.02, outlier_frac=0.001, device=DEV)
+        X = inputs.activation(M, K, seed=4400 + 10 * seed + i, device=DEV)
+        rows = np.unique(np.concatenate([[0, N - 1], rng.choice(N, size=min(N, 32), replace=False)]))
+        ridx = torch.from_numpy(rows).to(DEV)
+        codes_o, scales_o = O.quantize(to_np16(W[ridx]))
+        hi, lo, sc = _quant(W)
+        Y = P.fp6_linear(X, hi, lo, sc, N, K)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np16(sc[ridx]), scales_o), (M, N, K)
+        assert_y_close(Y[:, ridx], O.linear(to_np16(X), codes_o, scales_o), (M, N, K))
