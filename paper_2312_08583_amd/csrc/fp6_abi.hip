@@ -16,10 +16,10 @@ static bool shape_ok(int64_t N, int64_t K)
            K <= (int64_t)1 << 30 && N * K <= (int64_t)1 << 40;
 }
 
-// Number of K-slices for the decode family (measured on MI355X at M = 1).  The stream wants at
-// least one workgroup per compute unit; beyond ~1.5 per unit more slices only add to the tail,
-// where the slices' partial sums meet.  Two slices meet pairwise, which is cheaper than any
-// larger number, so two is taken whenever it fills the chip.  Every wavefront keeps >= 2 tiles.
+// Number of K-slices for the decode family where the cost model below does not apply: layers of 256 channel
+// blocks or more at up to 16 rows of X (measured on MI355X at M = 1: no split from 384 blocks on; below, two
+// slices, which meet pairwise - cheaper than any larger number), eight-wavefront workgroups, very short K.
+// Every wavefront keeps >= 2 tiles.
 static int pick_decode_split(int64_t units, int64_t ktiles, int waves)
 {
     if (units >= 384) return 1;
