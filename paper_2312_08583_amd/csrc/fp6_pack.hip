@@ -48,30 +48,27 @@ __global__ __launch_bounds__(256) void block_scale_kernel(const uint16_t* __rest
 // q = |w|/S is one correctly rounded fp32 division: a quotient that is not exactly a
 // grid midpoint is at least 2^-17 (relative) away from it, far more than the 2^-24 the
 // division can move it, and an exact midpoint divides exactly - so rounding q decides
-// exactly as rounding the real quotient would.  On the E3M2 grid the spacing inside
-// the binade of q is 2^(e-2) (1/16 below 0.25), so the rounding is one rint of q/spacing.
-// MB = mantissa bits: 2 for E3M2 (spacing 2^(e-2), largest value 28), 1 for E3M1 (2^(e-1), 24).
+// exactly as rounding the real quotient would.  The rounding itself works on the bit pattern
+// of q.  From 0.25 up the code is the top of that pattern: exponent field and the first MB
+// mantissa bits, rounded to nearest even in place (half a unit minus one, plus the last kept
+// bit, is added below them; a carry runs into the exponent as it should), re-biased from 127
+// to 3.  Below 0.25 the codes count multiples of 2^-(2+MB): adding 2^(21-MB) makes the fp32
+// addition round q to that spacing (to nearest even) and leaves the count in the low bits.
+// MB = mantissa bits: 2 for E3M2 (largest value 28), 1 for E3M1 (24).
 template <int MB = 2>
 __device__ __forceinline__ uint32_t e3m2_code(uint16_t wbits, float S)
 {
     const uint32_t sign = (wbits >> 15) << (3 + MB);
     if (S == 0.0f) return sign;
-    float a = (float)__builtin_bit_cast(_Float16, (uint16_t)(wbits & 0x7FFFu));
-    float q = fminf(a / S, MB == 2 ? 28.0f : 24.0f);
-    int e = (int)((__builtin_bit_cast(uint32_t, q) >> 23) & 0xFF) - 127;   // floor(log2 q), q normal
-    e = max(e, -2);
-    float inv_step = __builtin_bit_cast(float, (uint32_t)(127 - (e - MB)) << 23);   // 2^-(e-MB)
-    float step = __builtin_bit_cast(float, (uint32_t)(127 + (e - MB)) << 23);
-    float v = rintf(q * inv_step) * step;          // exact products (powers of two)
-    uint32_t vb = __builtin_bit_cast(uint32_t, v);
-    uint32_t mag;
-    if (v < 0.25f) {
-        mag = (uint32_t)(v * (float)(4 << MB));    // subnormal codes 0 .. 2^MB - 1
-    } else {
-        uint32_t E = ((vb >> 23) & 0xFF) - 124;    // exponent + bias 3
-        mag = (E << MB) | ((vb >> (23 - MB)) & ((1u << MB) - 1u));
-    }
-    return sign | mag;
+    const float a = (float)__builtin_bit_cast(_Float16, (uint16_t)(wbits & 0x7FFFu));
+    const float q = fminf(a / S, MB == 2 ? 28.0f : 24.0f);
+    constexpr int kDrop = 23 - MB;                               // mantissa bits of q below the code
+    const uint32_t b = __builtin_bit_cast(uint32_t, q);
+    const uint32_t top = (b + ((1u << (kDrop - 1)) - 1u) + ((b >> kDrop) & 1u)) >> kDrop;
+    const uint32_t normal = top - (124u << MB);                  // (exponent + 3) << MB | mantissa
+    const float t = q + (float)(1u << (21 - MB));                // spacing 2^-(2+MB) in that binade
+    const uint32_t sub = __builtin_bit_cast(uint32_t, t) & 7u;   // 0 .. 2^MB (the last one is 0.25 itself)
+    return sign | (q < 0.25f ? sub : normal);
 }
 
 // One thread = one lane slot of one tile (64 weights): reads its eight 8-element runs of

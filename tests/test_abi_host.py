@@ -111,17 +111,18 @@ def _scale_fp32(amax16: np.ndarray) -> np.ndarray:
 
 
 def _codes_fp32(w16: np.ndarray, S16: np.float16) -> np.ndarray:
+    """The quantizer kernel's arithmetic, operation by operation, in numpy float32 / uint32."""
     sign = (w16.view(np.uint16) >> 15).astype(np.uint8) << 5
     S = np.float32(S16)
     if S == 0:
         return sign
     q = np.minimum(np.abs(w16).astype(np.float32) / S, np.float32(28.0))
-    e = np.maximum(((q.view(np.uint32) >> 23) & 0xFF).astype(np.int32) - 127, -2)
-    step = np.ldexp(np.float32(1.0), e - 2).astype(np.float32)
-    v = (np.rint(q / step) * step).astype(np.float32)
-    vb = v.view(np.uint32)
-    mag = np.where(v < 0.25, (v * 16).astype(np.uint32), ((((vb >> 23) & 0xFF) - 124) << 2) | ((vb >> 21) & 3))
-    return sign | mag.astype(np.uint8)
+    b = q.view(np.uint32)
+    top = (b + np.uint32((1 << 20) - 1) + ((b >> 21) & 1)) >> 21          # nearest even on the bit pattern
+    normal = top - np.uint32(124 << 2)
+    t = (q + np.float32(1 << 19)).astype(np.float32)                       # multiples of 1/16, nearest even
+    sub = t.view(np.uint32) & 7
+    return sign | np.where(q < np.float32(0.25), sub, normal).astype(np.uint8)
 
 
 def test_fp32_scale_division_matches_exact_for_every_amax():
