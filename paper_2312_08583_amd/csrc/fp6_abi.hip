@@ -119,14 +119,13 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
     // the ablations exist for the default kernel configurations only
     if (hint_dequant > 2 || (hint_dequant && (hint_waves || hint_depth))) return false;
     if (hint_half && variant != FP6_VARIANT_DECODE) return false;
-    if (hint_gbn && (variant != FP6_VARIANT_GEMM || format == kE3M1 || block || hint_dequant || hint_waves ||
-                     (hint_gbn != 8 && hint_gbn != 4)))
+    if (hint_gbn && (variant != FP6_VARIANT_GEMM || hint_dequant || hint_waves || (hint_gbn != 8 && hint_gbn != 4)))
         return false;
     // 64-channel blocks (= wavefronts) per workgroup of the tiled kernel.  Eight share the activations best;
     // four give twice the workgroups where there are few (measured: 40 against 47 us at 32 x 28672 x 8192, 24
     // against 30 us at 512 x 1024 x 8192, 20.7 against 30 us at 128 x 5120 x 5120).  The cost model below chooses.
     const bool plain = format == kE3M2 && !block && !hint_dequant;
-    const bool narrow_ok = (plain || layout2(format)) && variant == FP6_VARIANT_GEMM;
+    const bool narrow_ok = !hint_dequant && variant == FP6_VARIANT_GEMM;      // every format but the ablations
     int64_t gbn = hint_gbn ? hint_gbn : 8;
     p.gbn = (int)gbn;
     int64_t tiles, regs_per_tile;

@@ -18,10 +18,19 @@ hipError_t launch_gemm_variant(const LinearPlan& p, const uint16_t* X, int64_t M
         if (p.block_m == 64) return launch_gemm_t<64, 4, 1, kBiasShift, false, kE3M2H>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
         return launch_gemm_t<128, 3, 1, kBiasShift, false, kE3M2H>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     }
+    if (p.format == kE3M1 && p.gbn == 4) {
+        if (p.block_m == 32) return launch_gemm_t<32, 4, 1, kBiasShift, false, kE3M1, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        if (p.block_m == 64) return launch_gemm_t<64, 3, 1, kBiasShift, false, kE3M1, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        return launch_gemm_t<128, 2, 1, kBiasShift, false, kE3M1, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+    }
     if (p.format == kE3M1) {
         if (p.block_m == 32) return launch_gemm_t<32, 4, 1, kBiasShift, false, kE3M1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
         if (p.block_m == 64) return launch_gemm_t<64, 4, 1, kBiasShift, false, kE3M1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
         return launch_gemm_t<128, 3, 1, kBiasShift, false, kE3M1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+    }
+    if (p.gshift >= 0 && p.gbn == 4) {
+        if (p.block_m == 32) return launch_gemm_t<32, 4, 1, kBiasShift, true, kE3M2, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+        return launch_gemm_t<64, 3, 1, kBiasShift, true, kE3M2, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     }
     if (p.gshift >= 0) {
         if (p.block_m == 32) return launch_gemm_t<32, 4, 1, kBiasShift, true>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
