@@ -60,7 +60,8 @@ static void plan_small_decode(int64_t M, int64_t nblocks, int64_t ktiles, int ti
             const double rounds = (double)((wgs + 255) / 256);
             const bool rows16 = M <= 16;
             const double stream = bytes / (rows16 ? 6.2e6 : 3.87e6);
-            const double rate = rows16 ? (half ? 29e3 : 35e3) : 35e3 * pow(16.0 / (double)M, 0.565);
+            // (FP5 half tiles fetch the 1-bit plane four bytes a lane: 22 GB/s separates 8192 x 8192, where they win, from 8192 x 22016, where they lose)
+            const double rate = rows16 ? (half ? (tile_bytes == 3072 ? 29e3 : 22e3) : 35e3) : 35e3 * pow(16.0 / (double)M, 0.565);
             const double unit = rounds * (bytes / (double)wgs) / rate;
             const double meet = d == 1 ? 0.0
                                 : rows16 ? (d == 2 ? 1.3 : 1.4 + 0.03 * (double)d)
@@ -131,8 +132,8 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
     int64_t tiles, regs_per_tile;
     if (variant == FP6_VARIANT_DECODE) {
         // half-tile workgroups (32 channels): plain FP6 with row scales and the bias-shift unpack only
-        const bool half_ok = format == kE3M2 && !block && !hint_dequant && (!hint_waves || hint_waves == 4) &&
-                             2 * nblocks <= kMaxCounters;
+        const bool half_ok = (format == kE3M2 || format == kE3M1) && !block && !hint_dequant &&
+                             (!hint_waves || hint_waves == 4) && 2 * nblocks <= kMaxCounters;
         if (hint_half > 2 || (hint_half == 1 && !half_ok)) return false;
         // Measured at M <= 4: half-tile workgroups win where they give about one workgroup per compute unit with
         // no K-split or a two-way one (10.3 against 11.6 us at 8192 x 8192); with more workgroups per unit they lose.

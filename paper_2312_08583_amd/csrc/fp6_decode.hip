@@ -278,16 +278,22 @@ struct HalfRaw {
     u32x2 lo;
 };
 
+// FP5: the 1-bit plane has 8 bytes per lane and tile, one dword per half (fragments 4h .. 4h+3).
+template <int FMT>
 __device__ __forceinline__ HalfRaw load_half(const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
                                              size_t tile_index, int lane, int h)
 {
     HalfRaw r;
     r.hi = __builtin_nontemporal_load(hi + tile_index * kHiTileVec + h * 64 + lane);
-    r.lo = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(lo + tile_index * kLoTileVec + lane) + h);
+    if (FMT == kE3M1) {
+        r.lo = u32x2{__builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(lo) + (tile_index * 64 + lane) * 2 + h), 0u};
+    } else {
+        r.lo = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(lo + tile_index * kLoTileVec + lane) + h);
+    }
     return r;
 }
 
-template <int WAVES, int D>
+template <int WAVES, int D, int FMT = kE3M2>
 __global__ __launch_bounds__(WAVES * 64) void decode_half_kernel(
     const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
     const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
@@ -316,7 +322,8 @@ __global__ __launch_bounds__(WAVES * 64) void decode_half_kernel(
     auto mac = [&](const HalfRaw& r, const XFrag& x) {
 #pragma unroll
         for (int f = 0; f < 4; f++) {
-            half8 w = unpack_fragment<kBiasShift>(r.hi[f], r.lo[f >> 1] >> (4 * (f & 1)));
+            half8 w = FMT == kE3M1 ? unpack_fragment_e3m1(r.hi[f], r.lo[0], f)
+                                   : unpack_fragment<kBiasShift>(r.hi[f], r.lo[f >> 1] >> (4 * (f & 1)));
             acc[f >> 1] = mfma16x16x32(w, (f & 1) ? x.q1 : x.q0, acc[f >> 1]);
         }
     };
@@ -329,7 +336,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_half_kernel(
 #pragma unroll
         for (int u = 0; u < D - 1; u++) {
             const int k = kt0 + min(u, cnt - 1) * WAVES;
-            raw[u] = load_half(hi, lo, tile0 + k, lane, h);
+            raw[u] = load_half<FMT>(hi, lo, tile0 + k, lane, h);
             xf[u] = load_x(xrow, k);
         }
         int j0 = 0;
@@ -337,7 +344,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_half_kernel(
 #pragma unroll
             for (int u = 0; u < D; u++) {
                 const int k = kt0 + (j0 + u + D - 1) * WAVES;
-                raw[(u + D - 1) % D] = load_half(hi, lo, tile0 + k, lane, h);
+                raw[(u + D - 1) % D] = load_half<FMT>(hi, lo, tile0 + k, lane, h);
                 xf[(u + D - 1) % D] = load_x(xrow, k);
                 mac(raw[u], xf[u]);
             }
@@ -348,7 +355,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_half_kernel(
             if (j < cnt) {
                 if (j + D - 1 < cnt) {
                     const int k = kt0 + (j + D - 1) * WAVES;
-                    raw[(v + D - 1) % D] = load_half(hi, lo, tile0 + k, lane, h);
+                    raw[(v + D - 1) % D] = load_half<FMT>(hi, lo, tile0 + k, lane, h);
                     xf[(v + D - 1) % D] = load_x(xrow, k);
                 }
                 mac(raw[v % D], xf[v % D]);
@@ -414,7 +421,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_half_kernel(
     }
 }
 
-template <int WAVES, int D>
+template <int WAVES, int D, int FMT = kE3M2>
 static hipError_t launch_decode_half_t(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
                                        const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                                        hipStream_t stream)
@@ -424,7 +431,7 @@ static hipError_t launch_decode_half_t(const LinearPlan& p, const uint16_t* X, i
     unsigned long long* slots = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(workspace) + kCounterBytes);
     const int64_t units = (N / kTile) * p.split_k;
     const unsigned grid = (unsigned)((units + 7) / 8 * 16);
-    hipLaunchKernelGGL((decode_half_kernel<WAVES, D>), dim3(grid), dim3(WAVES * 64), 0, stream, X, (int)M,
+    hipLaunchKernelGGL((decode_half_kernel<WAVES, D, FMT>), dim3(grid), dim3(WAVES * 64), 0, stream, X, (int)M,
                        (const u32x4*)hi, (const u32x4*)lo, scales, (int)N, (int)K, Y, partials, counters, slots,
                        p.split_k, p.pairwise);
     return hipGetLastError();
@@ -453,6 +460,7 @@ hipError_t launch_decode(const LinearPlan& p, const uint16_t* X, int64_t M, cons
 {
     if (p.block_m == 32) return launch_decode_t<4, 4, kBiasShift, false, kE3M2, 2>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     if (p.block_m == 64) return launch_decode_t<4, 3, kBiasShift, false, kE3M2, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
+    if (p.half_tiles && p.format == kE3M1) return launch_decode_half_t<4, 4, kE3M1>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     if (p.half_tiles) {
         if (p.depth == 8) return launch_decode_half_t<4, 8>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
         if (p.depth == 6) return launch_decode_half_t<4, 6>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);

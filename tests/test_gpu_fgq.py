@@ -60,7 +60,10 @@ def test_fgq_with_block_k_equals_the_row_wise_calls():
                                              (16, B.FP6_VARIANT_DECODE, 4), (1, B.FP6_VARIANT_DECODE, 0),
                                              (17, B.FP6_VARIANT_GEMM, 1), (40, B.FP6_VARIANT_GEMM, 2),
                                              (100, B.FP6_VARIANT_GEMM, 1), (100, B.FP6_VARIANT_GEMM, 3),
-                                             (8, B.FP6_VARIANT_GEMM, 1), (300, B.FP6_VARIANT_AUTO, 0)])
+                                             (8, B.FP6_VARIANT_GEMM, 1), (300, B.FP6_VARIANT_AUTO, 0),
+                                             (40, B.FP6_VARIANT_GEMM | B.FP6_HINT_WIDTH(4) | B.FP6_HINT_BLOCK_M(32), 2),
+                                             (100, B.FP6_VARIANT_GEMM | B.FP6_HINT_WIDTH(4) | B.FP6_HINT_BLOCK_M(64), 3),
+                                             (100, B.FP6_VARIANT_GEMM | B.FP6_HINT_WIDTH(8) | B.FP6_HINT_BLOCK_M(64), 1)])
 def test_fgq_linear_vs_oracle(block, M, variant, split):
     N, K = 640, 1536
     W = inputs.weight(N, K, seed=1400 + block, sigma=0.02, outlier_frac=0.001, device=DEV)

@@ -61,7 +61,10 @@ def test_fp5_planes_round_trip_for_arbitrary_codes():
 
 
 @pytest.mark.parametrize("variant,split", [(B.FP6_VARIANT_DECODE, 1), (B.FP6_VARIANT_DECODE, 2),
-                                           (B.FP6_VARIANT_GEMM, 1), (B.FP6_VARIANT_GEMM, 2)])
+                                           (B.FP6_VARIANT_DECODE | B.FP6_HINT_HALF(1), 1),
+                                           (B.FP6_VARIANT_DECODE | B.FP6_HINT_HALF(1), 2),
+                                           (B.FP6_VARIANT_GEMM, 1), (B.FP6_VARIANT_GEMM, 2),
+                                           (B.FP6_VARIANT_GEMM | B.FP6_HINT_WIDTH(4), 2)])
 def test_fp5_one_hot_rows_read_back_dequantized_weights_bit_exact(variant, split):
     N, K = 128, 256
     rng = np.random.default_rng(13)
@@ -78,7 +81,7 @@ def test_fp5_one_hot_rows_read_back_dequantized_weights_bit_exact(variant, split
         X = torch.zeros((len(cols), K), dtype=torch.float16, device=DEV)
         for m, k in enumerate(cols):
             X[m, k] = 1.0
-        if variant == B.FP6_VARIANT_GEMM:
+        if (variant & 0xFF) == B.FP6_VARIANT_GEMM:
             X = torch.cat([X, X, X[:1]])
         Y = to_np16(P.fp5_linear(X, hi_d, lo_d, sc_d, N, K, variant, split))
         Y = np.where((Y & 0x7FFF) == 0, 0, Y).astype(np.uint16)
@@ -89,7 +92,13 @@ def test_fp5_one_hot_rows_read_back_dequantized_weights_bit_exact(variant, split
 @pytest.mark.parametrize("M,variant,split", [(1, B.FP6_VARIANT_AUTO, 0), (1, B.FP6_VARIANT_DECODE, 1),
                                              (7, B.FP6_VARIANT_DECODE, 4), (16, B.FP6_VARIANT_DECODE, 3),
                                              (17, B.FP6_VARIANT_GEMM, 1), (40, B.FP6_VARIANT_GEMM, 2),
-                                             (100, B.FP6_VARIANT_GEMM, 1), (300, B.FP6_VARIANT_AUTO, 0)])
+                                             (100, B.FP6_VARIANT_GEMM, 1), (300, B.FP6_VARIANT_AUTO, 0),
+                                             (1, B.FP6_VARIANT_DECODE | B.FP6_HINT_HALF(1), 1),
+                                             (3, B.FP6_VARIANT_DECODE | B.FP6_HINT_HALF(1), 2),
+                                             (4, B.FP6_VARIANT_DECODE | B.FP6_HINT_HALF(1), 4),
+                                             (16, B.FP6_VARIANT_DECODE | B.FP6_HINT_HALF(1) | B.FP6_HINT_MEET(1), 2),
+                                             (70, B.FP6_VARIANT_GEMM | B.FP6_HINT_WIDTH(4) | B.FP6_HINT_BLOCK_M(64), 3),
+                                             (130, B.FP6_VARIANT_GEMM | B.FP6_HINT_WIDTH(4) | B.FP6_HINT_BLOCK_M(128), 2)])
 def test_fp5_linear_vs_oracle(M, variant, split):
     N, K = 640, 1536
     W = inputs.weight(N, K, seed=1600, sigma=0.02, outlier_frac=0.001, device=DEV)
