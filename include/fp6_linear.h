@@ -189,6 +189,36 @@ int fp6_linear_variant(const uint16_t *X, int64_t M, const void *hi_plane, const
                        int variant, int split_k);
 
 /*
+ * What a call of the hot path would launch (no passage of the paper: the kernel family, tile and
+ * K-split are this library's choices for gfx950).  Host-only, touches no GPU: it runs the same
+ * planner as fp6_linear / fp6_linear_variant / fp6_linear_fgq / fp5_linear / fp6_linear_v2(_bf16)
+ * and reports the result, so that a change of the planner shows up in tests and benchmark rows.
+ *   format   FP6_FORMAT_E3M2 (fp6_linear*), FP6_FORMAT_E3M1 (fp5_linear), FP6_FORMAT_E3M2_V2
+ *            (fp6_linear_v2), FP6_FORMAT_E3M2_V2_BF16 (fp6_linear_v2_bf16)
+ *   block    0 = one scale per row; else the fine-grained block (FP6_FORMAT_E3M2 only)
+ *   variant, split_k   as in fp6_linear_variant (0, 0 = what fp6_linear does)
+ * Errors: FP6_ERR_NULL (info), FP6_ERR_SHAPE, FP6_ERR_VARIANT (as the call itself would return).
+ */
+#define FP6_FORMAT_E3M2 6
+#define FP6_FORMAT_E3M1 5
+#define FP6_FORMAT_E3M2_V2 7
+#define FP6_FORMAT_E3M2_V2_BF16 8
+typedef struct fp6_plan_info {
+    int variant;            /* FP6_VARIANT_DECODE or FP6_VARIANT_GEMM                                   */
+    int split_k;            /* K-slices handled by separate workgroups (1 = K is not split)            */
+    int block_m;            /* rows of X per workgroup: gemm 32/64/128; decode 16, 32 or 64             */
+    int width;              /* 64-channel blocks per workgroup: gemm 8 or 4; decode 1                   */
+    int waves;              /* wavefronts per workgroup                                                */
+    int depth;              /* tiles (decode) or stages (gemm) in the prefetch ring                    */
+    int half_tiles;         /* decode: 1 = workgroups own 32 channels                                   */
+    int meeting;            /* how K-slices are added: 0 none, 1 arrival counter, 2 pairwise slots      */
+    int64_t workgroups;     /* launch grid                                                             */
+    size_t workspace_bytes; /* what the matching *_workspace_bytes call returns                        */
+} fp6_plan_info;
+int fp6_linear_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int variant, int split_k,
+                    fp6_plan_info *info);
+
+/*
  * Fine-grained quantization (Section 3, "FGQ"; Appendix A, block-k quantization): every
  * `block` consecutive elements of a row of W share one scale, S = RNE_fp16(max|w| / 28)
  * over the block (Eq. 3), instead of one scale per row.  In the linear layer the scale

@@ -55,7 +55,16 @@ EXPORTS = ["fp6_layout_version", "fp6_status_string", "fp6_packed_sizes", "fp6_q
            "fp6_dequantize_fgq", "fp6_linear_fgq_workspace_bytes", "fp6_linear_fgq", "fp5_packed_sizes",
            "fp5_quantize_pack", "fp5_unpack_codes", "fp5_dequantize", "fp5_linear_workspace_bytes", "fp5_linear",
            "fp6_quantize_pack_v2", "fp6_unpack_codes_v2", "fp6_dequantize_v2", "fp6_linear_v2_workspace_bytes",
-           "fp6_linear_v2", "fp6_linear_v2_bf16", "fp6_probe_read", "fp6_probe_mfma"]
+           "fp6_linear_v2", "fp6_linear_v2_bf16", "fp6_probe_read", "fp6_probe_mfma", "fp6_linear_plan"]
+
+FP6_FORMAT_E3M2, FP6_FORMAT_E3M1, FP6_FORMAT_E3M2_V2, FP6_FORMAT_E3M2_V2_BF16 = 6, 5, 7, 8
+
+
+class PlanInfo(ctypes.Structure):
+    """fp6_plan_info of the header."""
+    _fields_ = [("variant", ctypes.c_int), ("split_k", ctypes.c_int), ("block_m", ctypes.c_int), ("width", ctypes.c_int),
+                ("waves", ctypes.c_int), ("depth", ctypes.c_int), ("half_tiles", ctypes.c_int), ("meeting", ctypes.c_int),
+                ("workgroups", ctypes.c_int64), ("workspace_bytes", ctypes.c_size_t)]
 
 _LIB = None
 
@@ -130,6 +139,8 @@ def lib() -> ctypes.CDLL:
     L.fp6_probe_read.argtypes = [p, sz, ci, p, sz, p]
     L.fp6_probe_mfma.restype = ci
     L.fp6_probe_mfma.argtypes = [ci, ci, ci, ci, p, sz, p]
+    L.fp6_linear_plan.restype = ci
+    L.fp6_linear_plan.argtypes = [ci, i64, i64, i64, i64, ci, ci, ctypes.POINTER(PlanInfo)]
     _LIB = L
     return L
 
@@ -151,8 +162,28 @@ def _dev(t: torch.Tensor, dtype, what: str) -> int:
     return t.data_ptr()
 
 
+def _sized(t: torch.Tensor, dtype, what: str, numel: int) -> int:
+    """Device pointer of `t` after checking that it holds exactly `numel` elements: the C ABI sees pointers
+    only, so this is the one place where a buffer that is too small for (N, K) can be stopped."""
+    ptr = _dev(t, dtype, what)
+    if t.numel() != numel:
+        raise Fp6Error("%s holds %d elements, the shape needs %d" % (what, t.numel(), numel))
+    return ptr
+
+
 def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
+
+
+def _shape_ok(N: int, K: int) -> None:
+    if N <= 0 or K <= 0 or N % FP6_TILE or K % FP6_TILE:
+        raise Fp6Error("N and K must be positive multiples of %d" % FP6_TILE)
+
+
+def _planes(hi: torch.Tensor, lo: torch.Tensor, N: int, K: int, lo_div: int = 4) -> Tuple[int, int]:
+    """Pointers of the two planes, sized for [N, K]: N*K/2 bytes and N*K/lo_div bytes."""
+    _shape_ok(N, K)
+    return _sized(hi, torch.uint8, "hi_plane", N * K // 2), _sized(lo, torch.uint8, "lo_plane", N * K // lo_div)
 
 
 def fp6_layout_version() -> int:
@@ -165,32 +196,113 @@ def fp6_packed_sizes(N: int, K: int) -> Tuple[int, int, int]:
     return a.value, b.value, c.value
 
 
-def fp6_quantize_pack(W: torch.Tensor):
-    """W fp16 [N,K] on the GPU -> (hi_plane uint8 [N*K/2], lo_plane uint8 [N*K/4], scales fp16 [N])."""
+def fp5_packed_sizes(N: int, K: int) -> Tuple[int, int, int]:
+    a, b, c = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib().fp5_packed_sizes(N, K, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)), "fp5_packed_sizes")
+    return a.value, b.value, c.value
+
+
+def fp6_linear_plan(M: int, N: int, K: int, format: int = FP6_FORMAT_E3M2, block: int = 0,
+                    variant: int = FP6_VARIANT_AUTO, split_k: int = 0) -> dict:
+    """What the hot-path call for this shape would launch (host-only query; needs no GPU)."""
+    info = PlanInfo()
+    _check(lib().fp6_linear_plan(format, M, N, K, block, variant, split_k, ctypes.byref(info)), "fp6_linear_plan")
+    return {name: int(getattr(info, name)) for name, _ in PlanInfo._fields_}
+
+
+def plan_text(plan: dict) -> str:
+    """One-line summary of a plan for benchmark rows."""
+    fam = "decode" if plan["variant"] == FP6_VARIANT_DECODE else "gemm"
+    meet = ("", " counter", " pairwise")[plan["meeting"]]
+    if fam == "decode":
+        return "decode%s rows%d split%d%s wg%d" % (" half" if plan["half_tiles"] else "", plan["block_m"], plan["split_k"],
+                                                   meet, plan["workgroups"])
+    return "gemm %dx%d split%d%s wg%d" % (plan["block_m"], 64 * plan["width"], plan["split_k"], meet, plan["workgroups"])
+
+
+def new_workspace(nbytes: int, device) -> Optional[torch.Tensor]:
+    """Zero-filled workspace (the counters at its start must be zero before first use)."""
+    if nbytes == 0:
+        return None
+    return torch.zeros(nbytes, dtype=torch.uint8, device=device)
+
+
+# ---- offline step and test utilities: one marshalling routine per kind of call
+
+def _quantize_pack(name: str, W: torch.Tensor, sizes, block: int = 0):
     wp = _dev(W, torch.float16, "W")
+    if W.dim() != 2:
+        raise Fp6Error("W must be [N,K]")
     N, K = W.shape
-    hb, lb, _ = fp6_packed_sizes(N, K)
+    hb, lb, _ = sizes(N, K)
+    if block and (block <= 0 or K % block):
+        raise Fp6Error("block must divide K")
     hi = torch.empty(hb, dtype=torch.uint8, device=W.device)
     lo = torch.empty(lb, dtype=torch.uint8, device=W.device)
-    scales = torch.empty(N, dtype=torch.float16, device=W.device)
-    _check(lib().fp6_quantize_pack(wp, N, K, hi.data_ptr(), lo.data_ptr(), scales.data_ptr(), _stream()),
-           "fp6_quantize_pack")
+    scales = torch.empty((K // block, N) if block else (N,), dtype=torch.float16, device=W.device)
+    fn = getattr(lib(), name)
+    args = (wp, N, K) + ((block,) if block else ()) + (hi.data_ptr(), lo.data_ptr(), scales.data_ptr(), _stream())
+    _check(fn(*args), name)
     return hi, lo, scales
 
 
-def fp6_unpack_codes(hi: torch.Tensor, lo: torch.Tensor, N: int, K: int) -> torch.Tensor:
+def _unpack_codes(name: str, hi, lo, N: int, K: int, lo_div: int) -> torch.Tensor:
+    hp, lp = _planes(hi, lo, N, K, lo_div)
     codes = torch.empty((N, K), dtype=torch.uint8, device=hi.device)
-    _check(lib().fp6_unpack_codes(_dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"), N, K,
-                                  codes.data_ptr(), _stream()), "fp6_unpack_codes")
+    _check(getattr(lib(), name)(hp, lp, N, K, codes.data_ptr(), _stream()), name)
     return codes
 
 
-def fp6_dequantize(hi: torch.Tensor, lo: torch.Tensor, scales: torch.Tensor, N: int, K: int) -> torch.Tensor:
+def _dequantize(name: str, hi, lo, scales, N: int, K: int, lo_div: int, block: int = 0) -> torch.Tensor:
+    hp, lp = _planes(hi, lo, N, K, lo_div)
+    if block and (block <= 0 or K % block):
+        raise Fp6Error("block must divide K")
+    sp = _sized(scales, torch.float16, "scales", N * (K // block if block else 1))
     out = torch.empty((N, K), dtype=torch.float16, device=hi.device)
-    _check(lib().fp6_dequantize(_dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"),
-                                _dev(scales, torch.float16, "scales"), N, K, out.data_ptr(), _stream()),
-           "fp6_dequantize")
+    args = (hp, lp, sp, N, K) + ((block,) if block else ()) + (out.data_ptr(), _stream())
+    _check(getattr(lib(), name)(*args), name)
     return out
+
+
+def _linear(name: str, need, X, hi, lo, scales, N: int, K: int, out, workspace, tail=(), block: int = 0,
+            lo_div: int = 4, dtype=torch.float16) -> torch.Tensor:
+    """Marshal one hot-path call: every buffer is checked against the sizes that (M, N, K) imply."""
+    if not isinstance(X, torch.Tensor) or X.dim() != 2 or X.shape[1] != K or X.shape[0] < 1:
+        raise Fp6Error("X must be [M,K] with M >= 1")
+    xp = _dev(X, dtype, "X")
+    M = X.shape[0]
+    hp, lp = _planes(hi, lo, N, K, lo_div)
+    if block and (block <= 0 or K % block):
+        raise Fp6Error("block must divide K")
+    sp = _sized(scales, torch.float16, "scales", N * (K // block if block else 1))
+    if out is None:
+        out = torch.empty((M, N), dtype=dtype, device=X.device)
+    elif tuple(out.shape) != (M, N):
+        raise Fp6Error("Y must be [M,N] = [%d,%d], got %s" % (M, N, tuple(out.shape)))
+    yp = _dev(out, dtype, "Y")
+    if workspace is None:
+        workspace = new_workspace(int(need(M)), X.device)      # `need`: workspace bytes as a function of M
+    elif not (isinstance(workspace, torch.Tensor) and workspace.is_cuda and workspace.is_contiguous()
+              and workspace.dtype == torch.uint8):
+        raise Fp6Error("workspace must be a contiguous uint8 GPU tensor")
+    wp = workspace.data_ptr() if workspace is not None else None
+    wb = workspace.numel() if workspace is not None else 0
+    args = (xp, M, hp, lp, sp, N, K) + ((block,) if block else ()) + (yp, wp, wb, _stream()) + tuple(tail)
+    _check(getattr(lib(), name)(*args), name)
+    return out
+
+
+def fp6_quantize_pack(W: torch.Tensor):
+    """W fp16 [N,K] on the GPU -> (hi_plane uint8 [N*K/2], lo_plane uint8 [N*K/4], scales fp16 [N])."""
+    return _quantize_pack("fp6_quantize_pack", W, fp6_packed_sizes)
+
+
+def fp6_unpack_codes(hi: torch.Tensor, lo: torch.Tensor, N: int, K: int) -> torch.Tensor:
+    return _unpack_codes("fp6_unpack_codes", hi, lo, N, K, 4)
+
+
+def fp6_dequantize(hi: torch.Tensor, lo: torch.Tensor, scales: torch.Tensor, N: int, K: int) -> torch.Tensor:
+    return _dequantize("fp6_dequantize", hi, lo, scales, N, K, 4)
 
 
 def fp6_linear_workspace_bytes(M: int, N: int, K: int) -> int:
@@ -201,77 +313,34 @@ def fp6_linear_variant_workspace_bytes(M: int, N: int, K: int, variant: int, spl
     return int(lib().fp6_linear_variant_workspace_bytes(M, N, K, variant, split_k))
 
 
-def new_workspace(nbytes: int, device) -> Optional[torch.Tensor]:
-    """Zero-filled workspace (the counters at its start must be zero before first use)."""
-    if nbytes == 0:
-        return None
-    return torch.zeros(nbytes, dtype=torch.uint8, device=device)
-
-
 def fp6_linear_variant(X: torch.Tensor, hi: torch.Tensor, lo: torch.Tensor, scales: torch.Tensor, N: int, K: int,
                        variant: int = FP6_VARIANT_AUTO, split_k: int = 0, out: Optional[torch.Tensor] = None,
                        workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    xp = _dev(X, torch.float16, "X")
-    M = X.shape[0]
-    if X.dim() != 2 or X.shape[1] != K:
-        raise Fp6Error("X must be [M,K]")
-    if out is None:
-        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
-    need = fp6_linear_variant_workspace_bytes(M, N, K, variant, split_k)
-    if workspace is None:
-        workspace = new_workspace(need, X.device)
-    wp = workspace.data_ptr() if workspace is not None else None
-    wb = workspace.numel() if workspace is not None else 0
-    _check(lib().fp6_linear_variant(xp, M, _dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"),
-                                    _dev(scales, torch.float16, "scales"), N, K,
-                                    _dev(out, torch.float16, "Y"), wp, wb, _stream(), variant, split_k),
-           "fp6_linear_variant")
-    return out
+    need = lambda M: fp6_linear_variant_workspace_bytes(M, N, K, variant, split_k)
+    return _linear("fp6_linear_variant", need, X, hi, lo, scales, N, K, out, workspace, (variant, split_k))
 
 
 def fp6_linear(X: torch.Tensor, hi: torch.Tensor, lo: torch.Tensor, scales: torch.Tensor, N: int, K: int,
                out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     """Y[M,N] = X[M,K] x dequant(planes)^T with the row scales applied after the accumulation."""
-    xp = _dev(X, torch.float16, "X")
-    M = X.shape[0]
-    if X.dim() != 2 or X.shape[1] != K:
-        raise Fp6Error("X must be [M,K]")
-    if out is None:
-        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
-    if workspace is None:
-        workspace = new_workspace(fp6_linear_workspace_bytes(M, N, K), X.device)
-    wp = workspace.data_ptr() if workspace is not None else None
-    wb = workspace.numel() if workspace is not None else 0
-    _check(lib().fp6_linear(xp, M, _dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"),
-                            _dev(scales, torch.float16, "scales"), N, K, _dev(out, torch.float16, "Y"),
-                            wp, wb, _stream()), "fp6_linear")
-    return out
+    need = lambda M: fp6_linear_workspace_bytes(M, N, K)
+    return _linear("fp6_linear", need, X, hi, lo, scales, N, K, out, workspace)
 
 
 # ---- fine-grained (block-k) scales
 
 def fp6_quantize_pack_fgq(W: torch.Tensor, block: int):
     """W fp16 [N,K] -> (hi_plane, lo_plane, scales fp16 [K/block, N]): one scale per `block` elements of a row."""
-    wp = _dev(W, torch.float16, "W")
-    N, K = W.shape
-    hb, lb, _ = fp6_packed_sizes(N, K)
-    if block <= 0 or K % block:
+    if block <= 0:
         raise Fp6Error("block must divide K")
-    hi = torch.empty(hb, dtype=torch.uint8, device=W.device)
-    lo = torch.empty(lb, dtype=torch.uint8, device=W.device)
-    scales = torch.empty((K // block, N), dtype=torch.float16, device=W.device)
-    _check(lib().fp6_quantize_pack_fgq(wp, N, K, block, hi.data_ptr(), lo.data_ptr(), scales.data_ptr(), _stream()),
-           "fp6_quantize_pack_fgq")
-    return hi, lo, scales
+    return _quantize_pack("fp6_quantize_pack_fgq", W, fp6_packed_sizes, block)
 
 
 def fp6_dequantize_fgq(hi: torch.Tensor, lo: torch.Tensor, scales: torch.Tensor, N: int, K: int,
                        block: int) -> torch.Tensor:
-    out = torch.empty((N, K), dtype=torch.float16, device=hi.device)
-    _check(lib().fp6_dequantize_fgq(_dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"),
-                                    _dev(scales, torch.float16, "scales"), N, K, block, out.data_ptr(), _stream()),
-           "fp6_dequantize_fgq")
-    return out
+    if block <= 0:
+        raise Fp6Error("block must divide K")
+    return _dequantize("fp6_dequantize_fgq", hi, lo, scales, N, K, 4, block)
 
 
 def fp6_linear_fgq_workspace_bytes(M: int, N: int, K: int, block: int, variant: int = FP6_VARIANT_AUTO,
@@ -283,56 +352,25 @@ def fp6_linear_fgq(X: torch.Tensor, hi: torch.Tensor, lo: torch.Tensor, scales: 
                    block: int, variant: int = FP6_VARIANT_AUTO, split_k: int = 0,
                    out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     """Y[M,N] with block scales applied to each block's product sum before the accumulation."""
-    xp = _dev(X, torch.float16, "X")
-    M = X.shape[0]
-    if X.dim() != 2 or X.shape[1] != K:
-        raise Fp6Error("X must be [M,K]")
-    if out is None:
-        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
-    if workspace is None:
-        workspace = new_workspace(fp6_linear_fgq_workspace_bytes(M, N, K, block, variant, split_k), X.device)
-    wp = workspace.data_ptr() if workspace is not None else None
-    wb = workspace.numel() if workspace is not None else 0
-    _check(lib().fp6_linear_fgq(xp, M, _dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"),
-                                _dev(scales, torch.float16, "scales"), N, K, block, _dev(out, torch.float16, "Y"),
-                                wp, wb, _stream(), variant, split_k), "fp6_linear_fgq")
-    return out
+    if block <= 0:
+        raise Fp6Error("block must divide K")
+    need = lambda M: fp6_linear_fgq_workspace_bytes(M, N, K, block, variant, split_k)
+    return _linear("fp6_linear_fgq", need, X, hi, lo, scales, N, K, out, workspace, (variant, split_k), block=block)
 
 
 # ---- FP5 E3M1 ("4+1")
 
-def fp5_packed_sizes(N: int, K: int) -> Tuple[int, int, int]:
-    a, b, c = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
-    _check(lib().fp5_packed_sizes(N, K, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)), "fp5_packed_sizes")
-    return a.value, b.value, c.value
-
-
 def fp5_quantize_pack(W: torch.Tensor):
     """W fp16 [N,K] -> (hi_plane uint8 [N*K/2], lo_plane uint8 [N*K/8], scales fp16 [N])."""
-    wp = _dev(W, torch.float16, "W")
-    N, K = W.shape
-    hb, lb, _ = fp5_packed_sizes(N, K)
-    hi = torch.empty(hb, dtype=torch.uint8, device=W.device)
-    lo = torch.empty(lb, dtype=torch.uint8, device=W.device)
-    scales = torch.empty(N, dtype=torch.float16, device=W.device)
-    _check(lib().fp5_quantize_pack(wp, N, K, hi.data_ptr(), lo.data_ptr(), scales.data_ptr(), _stream()),
-           "fp5_quantize_pack")
-    return hi, lo, scales
+    return _quantize_pack("fp5_quantize_pack", W, fp5_packed_sizes)
 
 
 def fp5_unpack_codes(hi: torch.Tensor, lo: torch.Tensor, N: int, K: int) -> torch.Tensor:
-    codes = torch.empty((N, K), dtype=torch.uint8, device=hi.device)
-    _check(lib().fp5_unpack_codes(_dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"), N, K,
-                                  codes.data_ptr(), _stream()), "fp5_unpack_codes")
-    return codes
+    return _unpack_codes("fp5_unpack_codes", hi, lo, N, K, 8)
 
 
 def fp5_dequantize(hi: torch.Tensor, lo: torch.Tensor, scales: torch.Tensor, N: int, K: int) -> torch.Tensor:
-    out = torch.empty((N, K), dtype=torch.float16, device=hi.device)
-    _check(lib().fp5_dequantize(_dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"),
-                                _dev(scales, torch.float16, "scales"), N, K, out.data_ptr(), _stream()),
-           "fp5_dequantize")
-    return out
+    return _dequantize("fp5_dequantize", hi, lo, scales, N, K, 8)
 
 
 def fp5_linear_workspace_bytes(M: int, N: int, K: int, variant: int = FP6_VARIANT_AUTO, split_k: int = 0) -> int:
@@ -342,49 +380,22 @@ def fp5_linear_workspace_bytes(M: int, N: int, K: int, variant: int = FP6_VARIAN
 def fp5_linear(X: torch.Tensor, hi: torch.Tensor, lo: torch.Tensor, scales: torch.Tensor, N: int, K: int,
                variant: int = FP6_VARIANT_AUTO, split_k: int = 0, out: Optional[torch.Tensor] = None,
                workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    xp = _dev(X, torch.float16, "X")
-    M = X.shape[0]
-    if X.dim() != 2 or X.shape[1] != K:
-        raise Fp6Error("X must be [M,K]")
-    if out is None:
-        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
-    if workspace is None:
-        workspace = new_workspace(fp5_linear_workspace_bytes(M, N, K, variant, split_k), X.device)
-    wp = workspace.data_ptr() if workspace is not None else None
-    wb = workspace.numel() if workspace is not None else 0
-    _check(lib().fp5_linear(xp, M, _dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"),
-                            _dev(scales, torch.float16, "scales"), N, K, _dev(out, torch.float16, "Y"),
-                            wp, wb, _stream(), variant, split_k), "fp5_linear")
-    return out
+    need = lambda M: fp5_linear_workspace_bytes(M, N, K, variant, split_k)
+    return _linear("fp5_linear", need, X, hi, lo, scales, N, K, out, workspace, (variant, split_k), lo_div=8)
 
 
 # ---- FP6 in plane layout 2 (hardware conversion)
 
 def fp6_quantize_pack_v2(W: torch.Tensor):
-    wp = _dev(W, torch.float16, "W")
-    N, K = W.shape
-    hb, lb, _ = fp6_packed_sizes(N, K)
-    hi = torch.empty(hb, dtype=torch.uint8, device=W.device)
-    lo = torch.empty(lb, dtype=torch.uint8, device=W.device)
-    scales = torch.empty(N, dtype=torch.float16, device=W.device)
-    _check(lib().fp6_quantize_pack_v2(wp, N, K, hi.data_ptr(), lo.data_ptr(), scales.data_ptr(), _stream()),
-           "fp6_quantize_pack_v2")
-    return hi, lo, scales
+    return _quantize_pack("fp6_quantize_pack_v2", W, fp6_packed_sizes)
 
 
 def fp6_unpack_codes_v2(hi: torch.Tensor, lo: torch.Tensor, N: int, K: int) -> torch.Tensor:
-    codes = torch.empty((N, K), dtype=torch.uint8, device=hi.device)
-    _check(lib().fp6_unpack_codes_v2(_dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"), N, K,
-                                     codes.data_ptr(), _stream()), "fp6_unpack_codes_v2")
-    return codes
+    return _unpack_codes("fp6_unpack_codes_v2", hi, lo, N, K, 4)
 
 
 def fp6_dequantize_v2(hi: torch.Tensor, lo: torch.Tensor, scales: torch.Tensor, N: int, K: int) -> torch.Tensor:
-    out = torch.empty((N, K), dtype=torch.float16, device=hi.device)
-    _check(lib().fp6_dequantize_v2(_dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"),
-                                   _dev(scales, torch.float16, "scales"), N, K, out.data_ptr(), _stream()),
-           "fp6_dequantize_v2")
-    return out
+    return _dequantize("fp6_dequantize_v2", hi, lo, scales, N, K, 4)
 
 
 def fp6_linear_v2_workspace_bytes(M: int, N: int, K: int, variant: int = FP6_VARIANT_AUTO, split_k: int = 0) -> int:
@@ -394,21 +405,20 @@ def fp6_linear_v2_workspace_bytes(M: int, N: int, K: int, variant: int = FP6_VAR
 def fp6_linear_v2(X: torch.Tensor, hi: torch.Tensor, lo: torch.Tensor, scales: torch.Tensor, N: int, K: int,
                   variant: int = FP6_VARIANT_AUTO, split_k: int = 0, out: Optional[torch.Tensor] = None,
                   workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    xp = _dev(X, torch.float16, "X")
-    M = X.shape[0]
-    if X.dim() != 2 or X.shape[1] != K:
-        raise Fp6Error("X must be [M,K]")
-    if out is None:
-        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
-    if workspace is None:
-        workspace = new_workspace(fp6_linear_v2_workspace_bytes(M, N, K, variant, split_k), X.device)
-    wp = workspace.data_ptr() if workspace is not None else None
-    wb = workspace.numel() if workspace is not None else 0
-    _check(lib().fp6_linear_v2(xp, M, _dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"),
-                               _dev(scales, torch.float16, "scales"), N, K, _dev(out, torch.float16, "Y"),
-                               wp, wb, _stream(), variant, split_k), "fp6_linear_v2")
-    return out
+    need = lambda M: fp6_linear_v2_workspace_bytes(M, N, K, variant, split_k)
+    return _linear("fp6_linear_v2", need, X, hi, lo, scales, N, K, out, workspace, (variant, split_k))
 
+
+def fp6_linear_v2_bf16(X: torch.Tensor, hi: torch.Tensor, lo: torch.Tensor, scales: torch.Tensor, N: int, K: int,
+                       variant: int = FP6_VARIANT_AUTO, split_k: int = 0, out: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Layout-2 planes against bf16 activations; returns bf16."""
+    need = lambda M: fp6_linear_v2_workspace_bytes(M, N, K, variant, split_k)
+    return _linear("fp6_linear_v2_bf16", need, X, hi, lo, scales, N, K, out, workspace, (variant, split_k),
+                   dtype=torch.bfloat16)
+
+
+# ---- measurement probes (kernels that only read, or only issue MFMAs)
 
 def fp6_probe_read(buf: torch.Tensor, workgroups: int, sink: torch.Tensor) -> None:
     """One launch of the plain read kernel over all bytes of `buf` (a contiguous device tensor)."""
@@ -425,23 +435,3 @@ def fp6_probe_mfma(workgroups: int, iters: int, random_operands: bool, sink: tor
     _check(lib().fp6_probe_mfma(workgroups, iters, int(bool(random_operands)), int(bool(wide)), sink.data_ptr(),
                                 sink.numel() * sink.element_size(), _stream()), "fp6_probe_mfma")
     return workgroups * 4 * 8 * iters * 16384 * (2 if wide else 1)
-
-
-def fp6_linear_v2_bf16(X: torch.Tensor, hi: torch.Tensor, lo: torch.Tensor, scales: torch.Tensor, N: int, K: int,
-                       variant: int = FP6_VARIANT_AUTO, split_k: int = 0, out: Optional[torch.Tensor] = None,
-                       workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """Layout-2 planes against bf16 activations; returns bf16."""
-    xp = _dev(X, torch.bfloat16, "X")
-    M = X.shape[0]
-    if X.dim() != 2 or X.shape[1] != K:
-        raise Fp6Error("X must be [M,K]")
-    if out is None:
-        out = torch.empty((M, N), dtype=torch.bfloat16, device=X.device)
-    if workspace is None:
-        workspace = new_workspace(fp6_linear_v2_workspace_bytes(M, N, K, variant, split_k), X.device)
-    wp = workspace.data_ptr() if workspace is not None else None
-    wb = workspace.numel() if workspace is not None else 0
-    _check(lib().fp6_linear_v2_bf16(xp, M, _dev(hi, torch.uint8, "hi_plane"), _dev(lo, torch.uint8, "lo_plane"),
-                                    _dev(scales, torch.float16, "scales"), N, K, _dev(out, torch.bfloat16, "Y"),
-                                    wp, wb, _stream(), variant, split_k), "fp6_linear_v2_bf16")
-    return out

@@ -8,6 +8,11 @@
 
 namespace fp6 {
 
+// The runtime keeps the last error of any earlier call on this thread until somebody reads it; the launchers
+// report hipGetLastError() after their launch, so it is read (and dropped) once before, or a failure of an
+// unrelated earlier call would be reported as this call's.
+static void forget_earlier_errors() { (void)hipGetLastError(); }
+
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 static bool shape_ok(int64_t N, int64_t K)
@@ -154,7 +159,7 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
         p.block_m = M <= 16 ? 16 : (M <= 32 ? 32 : 64);
         if (M > 16 && (!plain || hint_waves || hint_depth || p.half_tiles || hint_meet == 2)) return false;
         p.waves = hint_waves ? hint_waves : 4;
-        p.depth = hint_depth ? hint_depth : 4;
+        p.depth = hint_depth ? hint_depth : (p.block_m == 64 ? 3 : 4);      // four row blocks per wavefront: ring of three
         tiles = nblocks;
         regs_per_tile = 16 * p.block_m;            // float4 per output tile (64 channels x block_m rows, fp32)
         p.split_k = split_k ? split_k
@@ -250,7 +255,6 @@ static size_t plan_workspace(const LinearPlan& p) { return p.split_k > 1 ? kZero
 }  // namespace fp6
 
 using namespace fp6;
-
 // block == 0: one scale per row
 static int quantize_pack_any(int format, const uint16_t* W, int64_t N, int64_t K, int64_t block, void* hi_plane, void* lo_plane,
                              uint16_t* scales, void* stream)
@@ -259,6 +263,7 @@ static int quantize_pack_any(int format, const uint16_t* W, int64_t N, int64_t K
     if (!shape_ok(N, K) || (block && !block_ok(K, block))) return FP6_ERR_SHAPE;
     if (block && N * (K / block) > ((int64_t)1 << 30)) return FP6_ERR_SHAPE;      // one workgroup per scale
     if (!aligned16(W) || !aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(scales)) return FP6_ERR_ALIGN;
+    forget_earlier_errors();
     return launch_quantize_pack(format, W, N, K, block ? block : K, hi_plane, lo_plane, scales, (hipStream_t)stream) ==
                    hipSuccess
                ? FP6_OK
@@ -271,6 +276,7 @@ static int dequantize_any(int format, const void* hi_plane, const void* lo_plane
     if (!hi_plane || !lo_plane || !scales || !W_hat) return FP6_ERR_NULL;
     if (!shape_ok(N, K) || (block && !block_ok(K, block))) return FP6_ERR_SHAPE;
     if (!aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(scales) || !aligned16(W_hat)) return FP6_ERR_ALIGN;
+    forget_earlier_errors();
     return launch_dequantize(format, hi_plane, lo_plane, scales, N, K, block ? block : K, W_hat, (hipStream_t)stream) ==
                    hipSuccess
                ? FP6_OK
@@ -297,6 +303,7 @@ static int linear_any(int format, const uint16_t* X, int64_t M, const void* hi_p
     if (!make_plan(format, M, N, K, block, variant, split_k, &p)) return FP6_ERR_VARIANT;
     const size_t need = plan_workspace(p);
     if (need > 0 && (!workspace || workspace_bytes < need)) return FP6_ERR_WORKSPACE;
+    forget_earlier_errors();
     hipError_t e = (p.variant == FP6_VARIANT_DECODE)
                        ? launch_decode(p, X, M, hi_plane, lo_plane, scales, N, K, Y, workspace, (hipStream_t)stream)
                        : launch_gemm(p, X, M, hi_plane, lo_plane, scales, N, K, Y, workspace, (hipStream_t)stream);
@@ -348,6 +355,7 @@ int fp6_unpack_codes(const void* hi_plane, const void* lo_plane, int64_t N, int6
     if (!hi_plane || !lo_plane || !codes) return FP6_ERR_NULL;
     if (!shape_ok(N, K)) return FP6_ERR_SHAPE;
     if (!aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(codes)) return FP6_ERR_ALIGN;
+    forget_earlier_errors();
     return launch_unpack_codes(kE3M2, hi_plane, lo_plane, N, K, codes, (hipStream_t)stream) == hipSuccess
                ? FP6_OK
                : FP6_ERR_HIP;
@@ -379,6 +387,36 @@ size_t fp6_linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
 size_t fp6_linear_fgq_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t block, int variant, int split_k)
 {
     return block > 0 ? workspace_any(kE3M2, M, N, K, block, variant, split_k) : 0;
+}
+
+int fp6_linear_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int variant, int split_k,
+                    fp6_plan_info* info)
+{
+    if (!info) return FP6_ERR_NULL;
+    if (format != kE3M2 && format != kE3M1 && format != kE3M2H && format != kE3M2B) return FP6_ERR_VARIANT;
+    if (M <= 0 || M > (int64_t)1 << 24 || !shape_ok(N, K) || block < 0) return FP6_ERR_SHAPE;
+    LinearPlan p;
+    if (!make_plan(format, M, N, K, block, variant, split_k, &p)) return FP6_ERR_VARIANT;
+    const int64_t nblocks = N / FP6_TILE;
+    info->variant = p.variant;
+    info->split_k = p.split_k;
+    info->block_m = p.block_m;
+    info->waves = p.waves;
+    info->depth = p.depth;
+    info->half_tiles = p.half_tiles;
+    info->meeting = p.split_k == 1 ? 0 : (p.pairwise ? 2 : 1);
+    if (p.variant == FP6_VARIANT_DECODE) {
+        // the grids of launch_decode_t / launch_decode_half_t
+        info->width = 1;
+        info->workgroups = p.half_tiles ? (nblocks * p.split_k + 7) / 8 * 16 : nblocks * p.split_k;
+    } else {
+        // the grid of launch_gemm_t
+        info->width = p.gbn;
+        const int64_t mblk = (M + p.block_m - 1) / p.block_m, nblk = (nblocks + p.gbn - 1) / p.gbn;
+        info->workgroups = mblk * ((nblk * p.split_k + 7) / 8 * 8);
+    }
+    info->workspace_bytes = plan_workspace(p);
+    return FP6_OK;
 }
 
 int fp6_linear_variant(const uint16_t* X, int64_t M, const void* hi_plane, const void* lo_plane,
@@ -418,6 +456,7 @@ int fp6_unpack_codes_v2(const void* hi_plane, const void* lo_plane, int64_t N, i
     if (!hi_plane || !lo_plane || !codes) return FP6_ERR_NULL;
     if (!shape_ok(N, K)) return FP6_ERR_SHAPE;
     if (!aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(codes)) return FP6_ERR_ALIGN;
+    forget_earlier_errors();
     return launch_unpack_codes(kE3M2H, hi_plane, lo_plane, N, K, codes, (hipStream_t)stream) == hipSuccess
                ? FP6_OK
                : FP6_ERR_HIP;
@@ -472,6 +511,7 @@ int fp5_unpack_codes(const void* hi_plane, const void* lo_plane, int64_t N, int6
     if (!hi_plane || !lo_plane || !codes) return FP6_ERR_NULL;
     if (!shape_ok(N, K)) return FP6_ERR_SHAPE;
     if (!aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(codes)) return FP6_ERR_ALIGN;
+    forget_earlier_errors();
     return launch_unpack_codes(kE3M1, hi_plane, lo_plane, N, K, codes, (hipStream_t)stream) == hipSuccess
                ? FP6_OK
                : FP6_ERR_HIP;

@@ -92,6 +92,7 @@ int fp6_probe_read(const void* buf, size_t bytes, int workgroups, void* sink, si
     if (((uintptr_t)buf & 15) || ((uintptr_t)sink & 3)) return FP6_ERR_ALIGN;
     if (bytes < 16 || workgroups < 1 || workgroups > (1 << 20)) return FP6_ERR_SHAPE;
     if (sink_bytes < (size_t)workgroups * 16) return FP6_ERR_WORKSPACE;
+    (void)hipGetLastError();      // drop an earlier call's error: the status below is this launch's
     hipLaunchKernelGGL(fp6::read_probe_kernel, dim3(workgroups), dim3(256), 0, (hipStream_t)stream,
                        (const fp6::u32x4*)buf, bytes / 16, (uint32_t*)sink);
     return hipGetLastError() == hipSuccess ? FP6_OK : FP6_ERR_HIP;
@@ -103,6 +104,7 @@ int fp6_probe_mfma(int workgroups, int iters, int random_operands, int wide, voi
     if ((uintptr_t)sink & 3) return FP6_ERR_ALIGN;
     if (workgroups < 1 || workgroups > (1 << 20) || iters < 1 || iters > (1 << 24)) return FP6_ERR_SHAPE;
     if (sink_bytes < (size_t)workgroups * 256 * sizeof(float)) return FP6_ERR_WORKSPACE;
+    (void)hipGetLastError();
     if (wide)
         hipLaunchKernelGGL(fp6::mfma_probe_kernel<true>, dim3(workgroups), dim3(256), 0, (hipStream_t)stream,
                            iters, random_operands, (float*)sink);

@@ -94,6 +94,52 @@ def test_workspace_bytes():
         assert B.fp6_linear_workspace_bytes(M, N, K) % 16 == 0
 
 
+def test_plan_query_agrees_with_the_calls_it_describes():
+    """fp6_linear_plan runs the planner of the hot-path calls: its workspace size is theirs, its launch is
+    consistent, and the families sit where the design puts them (decode up to 16 rows, tiled from 128 on)."""
+    from paper_2312_08583_amd import inputs
+    seen = set()
+    for wl, cfg in inputs.WORKLOADS.items():
+        for (_, N, K) in cfg["shapes"]:
+            for M in sorted(set(cfg["Ms"]) | {1, 3, 16, 17, 40, 64, 100, 512}):
+                p = B.fp6_linear_plan(M, N, K)
+                assert p["workspace_bytes"] == B.fp6_linear_workspace_bytes(M, N, K)
+                assert p["variant"] in (B.FP6_VARIANT_DECODE, B.FP6_VARIANT_GEMM)
+                assert p["split_k"] >= 1 and (K // 64) % p["split_k"] == 0
+                assert (p["meeting"] == 0) == (p["split_k"] == 1)
+                assert (p["workspace_bytes"] == 0) == (p["split_k"] == 1)
+                assert p["workgroups"] >= 1
+                if M <= 16:
+                    assert p["variant"] == B.FP6_VARIANT_DECODE and p["block_m"] == 16
+                if M >= 128:
+                    assert p["variant"] == B.FP6_VARIANT_GEMM and p["block_m"] in (32, 64, 128) and p["width"] in (4, 8)
+                if p["variant"] == B.FP6_VARIANT_DECODE:
+                    per = (N // 64) * p["split_k"]
+                    assert p["workgroups"] == ((per + 7) // 8 * 16 if p["half_tiles"] else per)
+                    assert M <= p["block_m"]
+                else:
+                    mblk = -(-M // p["block_m"])
+                    nblk = -(-(N // 64) // p["width"])
+                    assert p["workgroups"] == mblk * ((nblk * p["split_k"] + 7) // 8 * 8)
+                seen.add(p["variant"])
+                # a forced plan is reported as forced
+                q = B.fp6_linear_plan(M, N, K, variant=B.FP6_VARIANT_GEMM | B.FP6_HINT_BLOCK_M(32), split_k=1)
+                assert (q["variant"], q["block_m"], q["split_k"], q["meeting"]) == (B.FP6_VARIANT_GEMM, 32, 1, 0)
+                # the other formats and fine-grained scales plan too
+                for fmt in (B.FP6_FORMAT_E3M1, B.FP6_FORMAT_E3M2_V2, B.FP6_FORMAT_E3M2_V2_BF16):
+                    assert B.fp6_linear_plan(M, N, K, format=fmt)["workgroups"] >= 1
+                assert B.fp6_linear_plan(M, N, K, block=64)["workspace_bytes"] == B.fp6_linear_fgq_workspace_bytes(M, N, K, 64)
+    assert seen == {B.FP6_VARIANT_DECODE, B.FP6_VARIANT_GEMM}
+    L = B.lib()
+    info = B.PlanInfo()
+    assert L.fp6_linear_plan(6, 1, 64, 64, 0, 0, 0, None) == -1
+    assert L.fp6_linear_plan(6, 0, 64, 64, 0, 0, 0, ctypes.byref(info)) == -2
+    assert L.fp6_linear_plan(6, 1, 64, 100, 0, 0, 0, ctypes.byref(info)) == -2
+    assert L.fp6_linear_plan(9, 1, 64, 64, 0, 0, 0, ctypes.byref(info)) == -5
+    assert L.fp6_linear_plan(6, 65, 64, 64, 0, B.FP6_VARIANT_DECODE, 0, ctypes.byref(info)) == -5
+    assert L.fp6_linear_plan(6, 1, 64, 256, 96, 0, 0, ctypes.byref(info)) == -5          # block not 64 * 2^j
+
+
 def test_no_cpu_fallback():
     import torch
     W = torch.zeros((64, 64), dtype=torch.float16)
