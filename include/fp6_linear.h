@@ -19,7 +19,8 @@
  *     Y is [M, N] row-major.  There is no bias term.
  *   - fp16 data are passed as uint16_t bit patterns.
  *   - Every buffer pointer is a DEVICE pointer owned by the caller, 16-byte aligned.
- *     The library never allocates, frees or synchronises; it keeps no global state.
+ *     The library never allocates, frees or synchronises; it keeps no global state, with one
+ *     exception: the built-in scratch of fp6_linear_static (see there).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
  *     asynchronous on that stream.
  *   - N and K must be positive multiples of FP6_TILE (64).  M >= 1.
@@ -67,7 +68,8 @@ typedef enum {
     FP6_ERR_ALIGN = -3,      /* a buffer pointer is not 16-byte aligned                      */
     FP6_ERR_WORKSPACE = -4,  /* workspace missing or smaller than fp6_linear_workspace_bytes */
     FP6_ERR_VARIANT = -5,    /* kernel variant / split request not valid for this shape      */
-    FP6_ERR_HIP = -6         /* the HIP runtime reported a launch error                      */
+    FP6_ERR_HIP = -6,        /* the HIP runtime reported a launch error                      */
+    FP6_ERR_SCRATCH = -7     /* fp6_linear_static: the shape needs more than its built-in scratch */
 } fp6_status;
 
 /* kernel families behind fp6_linear (see fp6_linear_variant) */
@@ -148,6 +150,28 @@ size_t fp6_linear_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int fp6_linear(const uint16_t *X, int64_t M, const void *hi_plane, const void *lo_plane,
                const uint16_t *scales, int64_t N, int64_t K, uint16_t *Y,
                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * fp6_linear for callers that cannot hand over, or allocate, a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation, same kernels and
+ * same results as fp6_linear(X, M, ..., Y, workspace, ...); the K-slices meet in
+ * FP6_STATIC_SCRATCH_BYTES (64 MiB) of device memory that belongs to the library: a static device
+ * array, one copy per GPU the library is used on, held until the process ends.  The call allocates
+ * and frees nothing and never synchronises.
+ *   - A shape whose plan needs more scratch than that returns FP6_ERR_SCRATCH before anything is
+ *     launched (the need is what fp6_linear_workspace_bytes reports; e.g. M = 512 with K split four
+ *     ways over 8192 output channels does not fit): use fp6_linear with a workspace there.
+ *   - All calls on one GPU share that GPU's scratch, which keeps what the last call left: the
+ *     counters and slots at its start are cleared by the first call on a device (a small fill kernel
+ *     on `stream`, ahead of the first launch) and left zero by every call, the partial sums are
+ *     overwritten before they are read.  Calls that overlap in time on one GPU (different streams,
+ *     parallel graph branches) race on it and give wrong results: keep them on one stream.
+ *   - A caller that captures graphs makes its first call on each device outside any capture, so that
+ *     the one-time fill is executed rather than recorded.
+ */
+#define FP6_STATIC_SCRATCH_BYTES 67108864
+int fp6_linear_static(const uint16_t *X, int64_t M, const void *hi_plane, const void *lo_plane,
+                      const uint16_t *scales, int64_t N, int64_t K, uint16_t *Y, void *stream);
 
 /*
  * Same computation with the kernel family and the number of K-slices handled by separate

@@ -55,7 +55,7 @@ EXPORTS = ["fp6_layout_version", "fp6_status_string", "fp6_packed_sizes", "fp6_q
            "fp6_dequantize_fgq", "fp6_linear_fgq_workspace_bytes", "fp6_linear_fgq", "fp5_packed_sizes",
            "fp5_quantize_pack", "fp5_unpack_codes", "fp5_dequantize", "fp5_linear_workspace_bytes", "fp5_linear",
            "fp6_quantize_pack_v2", "fp6_unpack_codes_v2", "fp6_dequantize_v2", "fp6_linear_v2_workspace_bytes",
-           "fp6_linear_v2", "fp6_linear_v2_bf16", "fp6_probe_read", "fp6_probe_mfma", "fp6_linear_plan"]
+           "fp6_linear_v2", "fp6_linear_v2_bf16", "fp6_probe_read", "fp6_probe_mfma", "fp6_linear_plan", "fp6_linear_static"]
 
 FP6_FORMAT_E3M2, FP6_FORMAT_E3M1, FP6_FORMAT_E3M2_V2, FP6_FORMAT_E3M2_V2_BF16 = 6, 5, 7, 8
 
@@ -139,6 +139,8 @@ def lib() -> ctypes.CDLL:
     L.fp6_probe_read.argtypes = [p, sz, ci, p, sz, p]
     L.fp6_probe_mfma.restype = ci
     L.fp6_probe_mfma.argtypes = [ci, ci, ci, ci, p, sz, p]
+    L.fp6_linear_static.restype = ci
+    L.fp6_linear_static.argtypes = [p, i64, p, p, p, i64, i64, p, p]
     L.fp6_linear_plan.restype = ci
     L.fp6_linear_plan.argtypes = [ci, i64, i64, i64, i64, ci, ci, ctypes.POINTER(PlanInfo)]
     _LIB = L
@@ -325,6 +327,28 @@ def fp6_linear(X: torch.Tensor, hi: torch.Tensor, lo: torch.Tensor, scales: torc
     """Y[M,N] = X[M,K] x dequant(planes)^T with the row scales applied after the accumulation."""
     need = lambda M: fp6_linear_workspace_bytes(M, N, K)
     return _linear("fp6_linear", need, X, hi, lo, scales, N, K, out, workspace)
+
+
+FP6_STATIC_SCRATCH_BYTES = 67108864
+FP6_ERR_SCRATCH = -7
+
+
+def fp6_linear_static(X: torch.Tensor, hi: torch.Tensor, lo: torch.Tensor, scales: torch.Tensor, N: int, K: int,
+                      out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """fp6_linear on the library's built-in scratch: no workspace argument, nothing allocated by the call
+    (pass `out`; without it this wrapper, not the library, allocates Y)."""
+    if not isinstance(X, torch.Tensor) or X.dim() != 2 or X.shape[1] != K or X.shape[0] < 1:
+        raise Fp6Error("X must be [M,K] with M >= 1")
+    xp = _dev(X, torch.float16, "X")
+    M = X.shape[0]
+    hp, lp = _planes(hi, lo, N, K)
+    sp = _sized(scales, torch.float16, "scales", N)
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    elif tuple(out.shape) != (M, N):
+        raise Fp6Error("Y must be [M,N] = [%d,%d], got %s" % (M, N, tuple(out.shape)))
+    _check(lib().fp6_linear_static(xp, M, hp, lp, sp, N, K, _dev(out, torch.float16, "Y"), _stream()), "fp6_linear_static")
+    return out
 
 
 # ---- fine-grained (block-k) scales

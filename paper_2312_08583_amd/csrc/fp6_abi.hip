@@ -5,6 +5,7 @@
 #include "fp6_internal.hpp"
 
 #include <cmath>
+#include <mutex>
 
 namespace fp6 {
 
@@ -255,6 +256,44 @@ static size_t plan_workspace(const LinearPlan& p) { return p.split_k > 1 ? kZero
 }  // namespace fp6
 
 using namespace fp6;
+
+// ---- the workspace of fp6_linear_static: device memory that belongs to the library
+//
+// Each GPU the library runs on holds its own copy of this array, at its own address, until the process
+// ends.  In host code the array's name is only a handle for hipGetSymbolAddress: the device address is
+// looked up once per device (with that device current) and kept in scratch_ptr[]; kernels, and the fill
+// below, are given that address and never the name.
+static __device__ __align__(256) unsigned char scratch[FP6_STATIC_SCRATCH_BYTES];
+
+static constexpr int kMaxDevices = 64;
+static void* scratch_ptr[kMaxDevices];        // device address of `scratch` on device d (NULL: not looked up yet)
+static std::mutex scratch_mutex;
+
+// grid-stride fill with zeros, 16 bytes per thread and trip (a kernel, not a memset node: callers may be capturing)
+static __global__ void zero_fill_kernel(uint4* __restrict__ p, size_t n16)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = uint4{0u, 0u, 0u, 0u};
+}
+
+// Device address of this device's scratch; on the first call per device also clears the counters and slots
+// at its start (on `stream`, ahead of the caller's launch).  Returns NULL on a HIP error.
+static void* static_scratch(hipStream_t stream)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+        (void)hipGetLastError();
+        hipLaunchKernelGGL(zero_fill_kernel, dim3(256), dim3(256), 0, stream, reinterpret_cast<uint4*>(ptr), kZeroBytes / 16);
+        if (hipGetLastError() != hipSuccess) return nullptr;
+        scratch_ptr[dev] = ptr;
+    }
+    return scratch_ptr[dev];
+}
+
 // block == 0: one scale per row
 static int quantize_pack_any(int format, const uint16_t* W, int64_t N, int64_t K, int64_t block, void* hi_plane, void* lo_plane,
                              uint16_t* scales, void* stream)
@@ -324,6 +363,7 @@ const char* fp6_status_string(int status)
         case FP6_ERR_WORKSPACE: return "workspace missing or too small";
         case FP6_ERR_VARIANT: return "kernel variant or split_k not valid for this shape";
         case FP6_ERR_HIP: return "HIP launch error";
+        case FP6_ERR_SCRATCH: return "this shape needs more than the FP6_STATIC_SCRATCH_BYTES of built-in scratch: use fp6_linear with a workspace";
         default: return "unknown status";
     }
 }
@@ -432,6 +472,29 @@ int fp6_linear(const uint16_t* X, int64_t M, const void* hi_plane, const void* l
 {
     return linear_any(kE3M2, X, M, hi_plane, lo_plane, scales, N, K, 0, Y, workspace, workspace_bytes, stream,
                       FP6_VARIANT_AUTO, 0);
+}
+
+int fp6_linear_static(const uint16_t* X, int64_t M, const void* hi_plane, const void* lo_plane, const uint16_t* scales,
+                      int64_t N, int64_t K, uint16_t* Y, void* stream)
+{
+    if (!X || !hi_plane || !lo_plane || !scales || !Y) return FP6_ERR_NULL;
+    if (M <= 0 || M > (int64_t)1 << 24 || !shape_ok(N, K)) return FP6_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(hi_plane) || !aligned16(lo_plane) || !aligned16(scales) || !aligned16(Y))
+        return FP6_ERR_ALIGN;
+    LinearPlan p;
+    if (!make_plan(kE3M2, M, N, K, 0, FP6_VARIANT_AUTO, 0, &p)) return FP6_ERR_VARIANT;
+    const size_t need = plan_workspace(p);
+    if (need > (size_t)FP6_STATIC_SCRATCH_BYTES) return FP6_ERR_SCRATCH;
+    void* ws = nullptr;
+    if (need > 0) {
+        ws = static_scratch((hipStream_t)stream);
+        if (!ws) return FP6_ERR_HIP;
+    }
+    forget_earlier_errors();
+    hipError_t e = (p.variant == FP6_VARIANT_DECODE)
+                       ? launch_decode(p, X, M, hi_plane, lo_plane, scales, N, K, Y, ws, (hipStream_t)stream)
+                       : launch_gemm(p, X, M, hi_plane, lo_plane, scales, N, K, Y, ws, (hipStream_t)stream);
+    return e == hipSuccess ? FP6_OK : FP6_ERR_HIP;
 }
 
 int fp6_linear_fgq(const uint16_t* X, int64_t M, const void* hi_plane, const void* lo_plane, const uint16_t* scales,

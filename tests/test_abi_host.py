@@ -38,11 +38,11 @@ def test_packed_sizes_are_three_quarters_of_a_byte_per_weight():
 
 def test_status_strings():
     seen = set()
-    for st in range(0, -7, -1):
+    for st in range(0, -8, -1):
         s = B.fp6_status_string(st)
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 7
+    assert len(seen) == 8
     assert B.fp6_status_string(-99) == "unknown status"
 
 
