@@ -174,6 +174,37 @@ int fp6_linear_static(const uint16_t *X, int64_t M, const void *hi_plane, const 
                       const uint16_t *scales, int64_t N, int64_t K, uint16_t *Y, void *stream);
 
 /*
+ * Several independent layers on activations of the same height M in one call: the q, k, v projections
+ * of an attention block, the gate and up projections of a feed-forward block (Section 5.3 measures the
+ * kernel on exactly such feed-forward layers).  Each layer i computes what fp6_linear computes for
+ * (X_i, planes_i, scales_i) -> Y_i; the caller states by grouping them that no Y_i is read by another
+ * layer of the group and that the Y_i do not overlap.  For M <= 16 and layers that share K the group
+ * is ONE kernel launch: the workgroups of all layers start together, so a small layer (a 1024 x 8192
+ * k projection: 6 MB, mostly launch and tail when launched alone) rides in the shadow of a large one,
+ * and the channel blocks of all layers are planned as one list.  Otherwise the layers are launched one
+ * after another on `stream`, exactly as separate fp6_linear calls would be.  Results equal those of
+ * separate calls up to fp32 summation order (the K-split of a group may differ from a lone layer's).
+ *   problems   host array of `count` (1 .. FP6_GROUP_MAX) descriptions, read during the call only;
+ *              every pointer inside is a device pointer with the meaning it has in fp6_linear
+ *   workspace  device, >= fp6_linear_group_workspace_bytes(M, problems, count) bytes; same contract
+ *              as for fp6_linear (first FP6_WORKSPACE_ZERO_BYTES zero before first use, left zero)
+ * Errors as fp6_linear, found on the host before anything is launched; FP6_ERR_SHAPE also for a count
+ * outside 1 .. FP6_GROUP_MAX.
+ */
+#define FP6_GROUP_MAX 4
+typedef struct fp6_linear_problem {
+    const uint16_t *X;        /* fp16 bits [M,K]                      */
+    const void *hi_plane;     /* N*K/2 bytes                          */
+    const void *lo_plane;     /* N*K/4 bytes                          */
+    const uint16_t *scales;   /* fp16 bits [N]                        */
+    int64_t N, K;
+    uint16_t *Y;              /* fp16 bits [M,N]                      */
+} fp6_linear_problem;
+size_t fp6_linear_group_workspace_bytes(int64_t M, const fp6_linear_problem *problems, int count);
+int fp6_linear_group(int64_t M, const fp6_linear_problem *problems, int count, void *workspace,
+                     size_t workspace_bytes, void *stream);
+
+/*
  * Same computation with the kernel family and the number of K-slices handled by separate
  * workgroups chosen by the caller (tuning sweeps; tests that compare split and unsplit
  * results).  variant = FP6_VARIANT_AUTO and split_k = 0 reproduce fp6_linear.

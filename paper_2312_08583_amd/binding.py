@@ -55,9 +55,19 @@ EXPORTS = ["fp6_layout_version", "fp6_status_string", "fp6_packed_sizes", "fp6_q
            "fp6_dequantize_fgq", "fp6_linear_fgq_workspace_bytes", "fp6_linear_fgq", "fp5_packed_sizes",
            "fp5_quantize_pack", "fp5_unpack_codes", "fp5_dequantize", "fp5_linear_workspace_bytes", "fp5_linear",
            "fp6_quantize_pack_v2", "fp6_unpack_codes_v2", "fp6_dequantize_v2", "fp6_linear_v2_workspace_bytes",
-           "fp6_linear_v2", "fp6_linear_v2_bf16", "fp6_probe_read", "fp6_probe_mfma", "fp6_linear_plan", "fp6_linear_static"]
+           "fp6_linear_v2", "fp6_linear_v2_bf16", "fp6_probe_read", "fp6_probe_mfma", "fp6_linear_plan", "fp6_linear_static", "fp6_linear_group",
+           "fp6_linear_group_workspace_bytes"]
 
 FP6_FORMAT_E3M2, FP6_FORMAT_E3M1, FP6_FORMAT_E3M2_V2, FP6_FORMAT_E3M2_V2_BF16 = 6, 5, 7, 8
+
+
+FP6_GROUP_MAX = 4
+
+
+class LinearProblem(ctypes.Structure):
+    """fp6_linear_problem of the header."""
+    _fields_ = [("X", ctypes.c_void_p), ("hi_plane", ctypes.c_void_p), ("lo_plane", ctypes.c_void_p),
+                ("scales", ctypes.c_void_p), ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("Y", ctypes.c_void_p)]
 
 
 class PlanInfo(ctypes.Structure):
@@ -141,6 +151,10 @@ def lib() -> ctypes.CDLL:
     L.fp6_probe_mfma.argtypes = [ci, ci, ci, ci, p, sz, p]
     L.fp6_linear_static.restype = ci
     L.fp6_linear_static.argtypes = [p, i64, p, p, p, i64, i64, p, p]
+    L.fp6_linear_group_workspace_bytes.restype = sz
+    L.fp6_linear_group_workspace_bytes.argtypes = [i64, ctypes.POINTER(LinearProblem), ci]
+    L.fp6_linear_group.restype = ci
+    L.fp6_linear_group.argtypes = [i64, ctypes.POINTER(LinearProblem), ci, p, sz, p]
     L.fp6_linear_plan.restype = ci
     L.fp6_linear_plan.argtypes = [ci, i64, i64, i64, i64, ci, ci, ctypes.POINTER(PlanInfo)]
     _LIB = L
@@ -349,6 +363,55 @@ def fp6_linear_static(X: torch.Tensor, hi: torch.Tensor, lo: torch.Tensor, scale
         raise Fp6Error("Y must be [M,N] = [%d,%d], got %s" % (M, N, tuple(out.shape)))
     _check(lib().fp6_linear_static(xp, M, hp, lp, sp, N, K, _dev(out, torch.float16, "Y"), _stream()), "fp6_linear_static")
     return out
+
+
+def _group_array(layers, M: Optional[int] = None, outs=None):
+    """(X, hi, lo, scales, N, K) per layer -> checked ctypes array of fp6_linear_problem, M, list of Y tensors."""
+    if not 1 <= len(layers) <= FP6_GROUP_MAX:
+        raise Fp6Error("a group holds 1 to %d layers" % FP6_GROUP_MAX)
+    arr = (LinearProblem * len(layers))()
+    ys = []
+    for i, (X, hi, lo, scales, N, K) in enumerate(layers):
+        if not isinstance(X, torch.Tensor) or X.dim() != 2 or X.shape[1] != K or X.shape[0] < 1:
+            raise Fp6Error("X must be [M,K] with M >= 1")
+        if M is None:
+            M = X.shape[0]
+        if X.shape[0] != M:
+            raise Fp6Error("the layers of a group share M")
+        hp, lp = _planes(hi, lo, N, K)
+        Y = None if outs is None else outs[i]
+        if Y is None:
+            Y = torch.empty((M, N), dtype=torch.float16, device=X.device)
+        elif tuple(Y.shape) != (M, N):
+            raise Fp6Error("Y must be [M,N] = [%d,%d], got %s" % (M, N, tuple(Y.shape)))
+        arr[i] = LinearProblem(_dev(X, torch.float16, "X"), hp, lp, _sized(scales, torch.float16, "scales", N), N, K,
+                               _dev(Y, torch.float16, "Y"))
+        ys.append(Y)
+    return arr, M, ys
+
+
+def fp6_linear_group_workspace_bytes(M: int, shapes) -> int:
+    """Workspace for a group of layers given as (N, K) pairs (the pointers do not enter the size)."""
+    arr = (LinearProblem * len(shapes))()
+    for i, (N, K) in enumerate(shapes):
+        arr[i] = LinearProblem(16, 16, 16, 16, N, K, 16)        # aligned non-NULL placeholders, never dereferenced
+    return int(lib().fp6_linear_group_workspace_bytes(M, arr, len(shapes)))
+
+
+def fp6_linear_group(layers, outs=None, workspace: Optional[torch.Tensor] = None):
+    """Independent layers [(X, hi, lo, scales, N, K), ...] on activations of one height M in one call
+    (one launch for M <= 16 and a common K).  Returns the list of Y tensors."""
+    arr, M, ys = _group_array(layers, outs=outs)
+    need = int(lib().fp6_linear_group_workspace_bytes(M, arr, len(layers)))
+    if workspace is None:
+        workspace = new_workspace(need, ys[0].device)
+    elif not (isinstance(workspace, torch.Tensor) and workspace.is_cuda and workspace.is_contiguous()
+              and workspace.dtype == torch.uint8):
+        raise Fp6Error("workspace must be a contiguous uint8 GPU tensor")
+    wp = workspace.data_ptr() if workspace is not None else None
+    wb = workspace.numel() if workspace is not None else 0
+    _check(lib().fp6_linear_group(M, arr, len(layers), wp, wb, _stream()), "fp6_linear_group")
+    return ys
 
 
 # ---- fine-grained (block-k) scales

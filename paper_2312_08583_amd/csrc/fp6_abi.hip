@@ -349,6 +349,35 @@ static int linear_any(int format, const uint16_t* X, int64_t M, const void* hi_p
     return e == hipSuccess ? FP6_OK : FP6_ERR_HIP;
 }
 
+// A group of layers can share one launch if the streaming kernel serves them (M <= 16) and they have one K:
+// their channel blocks are then planned as the blocks of one layer with the summed N.
+static bool group_shares_a_launch(int64_t M, const fp6_linear_problem* pr, int count, LinearPlan* plan)
+{
+    if (count < 2 || M > 16) return false;
+    int64_t n_total = 0;
+    for (int i = 0; i < count; i++) {
+        if (pr[i].K != pr[0].K) return false;
+        n_total += pr[i].N;
+    }
+    if (!shape_ok(n_total, pr[0].K)) return false;
+    if (!make_plan(kE3M2, M, n_total, pr[0].K, 0, FP6_VARIANT_AUTO, 0, plan)) return false;
+    return plan->variant == FP6_VARIANT_DECODE && plan->block_m == 16 && plan->waves == 4 && plan->depth == 4;
+}
+
+static int group_check(int64_t M, const fp6_linear_problem* pr, int count)
+{
+    if (!pr) return FP6_ERR_NULL;
+    if (count < 1 || count > FP6_GROUP_MAX || M <= 0 || M > (int64_t)1 << 24) return FP6_ERR_SHAPE;
+    for (int i = 0; i < count; i++) {
+        if (!pr[i].X || !pr[i].hi_plane || !pr[i].lo_plane || !pr[i].scales || !pr[i].Y) return FP6_ERR_NULL;
+        if (!shape_ok(pr[i].N, pr[i].K)) return FP6_ERR_SHAPE;
+        if (!aligned16(pr[i].X) || !aligned16(pr[i].hi_plane) || !aligned16(pr[i].lo_plane) || !aligned16(pr[i].scales) ||
+            !aligned16(pr[i].Y))
+            return FP6_ERR_ALIGN;
+    }
+    return FP6_OK;
+}
+
 extern "C" {
 
 int fp6_layout_version(void) { return FP6_LAYOUT_VERSION; }
@@ -427,6 +456,47 @@ size_t fp6_linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
 size_t fp6_linear_fgq_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t block, int variant, int split_k)
 {
     return block > 0 ? workspace_any(kE3M2, M, N, K, block, variant, split_k) : 0;
+}
+
+size_t fp6_linear_group_workspace_bytes(int64_t M, const fp6_linear_problem* problems, int count)
+{
+    if (group_check(M, problems, count) != FP6_OK) return 0;
+    LinearPlan p;
+    if (group_shares_a_launch(M, problems, count, &p)) return plan_workspace(p);
+    size_t need = 0;
+    for (int i = 0; i < count; i++) {
+        const size_t n = workspace_any(kE3M2, M, problems[i].N, problems[i].K, 0, FP6_VARIANT_AUTO, 0);
+        need = n > need ? n : need;
+    }
+    return need;
+}
+
+int fp6_linear_group(int64_t M, const fp6_linear_problem* problems, int count, void* workspace, size_t workspace_bytes,
+                     void* stream)
+{
+    const int bad = group_check(M, problems, count);
+    if (bad != FP6_OK) return bad;
+    if (!aligned16(workspace)) return FP6_ERR_ALIGN;
+    const size_t need = fp6_linear_group_workspace_bytes(M, problems, count);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return FP6_ERR_WORKSPACE;
+    LinearPlan p;
+    if (group_shares_a_launch(M, problems, count, &p)) {
+        GroupLayer layers[FP6_GROUP_MAX];
+        for (int i = 0; i < count; i++)
+            layers[i] = GroupLayer{problems[i].X, problems[i].hi_plane, problems[i].lo_plane, problems[i].scales, problems[i].Y,
+                                   problems[i].N};
+        forget_earlier_errors();
+        return launch_decode_group(p, count, layers, M, problems[0].K, workspace, (hipStream_t)stream) == hipSuccess ? FP6_OK
+                                                                                                                    : FP6_ERR_HIP;
+    }
+    // one layer after another on the stream; they share the workspace in turn
+    for (int i = 0; i < count; i++) {
+        const int rc = linear_any(kE3M2, problems[i].X, M, problems[i].hi_plane, problems[i].lo_plane, problems[i].scales,
+                                  problems[i].N, problems[i].K, 0, problems[i].Y, workspace, workspace_bytes, stream,
+                                  FP6_VARIANT_AUTO, 0);
+        if (rc != FP6_OK) return rc;
+    }
+    return FP6_OK;
 }
 
 int fp6_linear_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int variant, int split_k,

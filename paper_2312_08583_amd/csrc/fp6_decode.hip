@@ -69,16 +69,18 @@ __device__ __forceinline__ void tile_mac(const TileRaw& r, const XFrag (&x)[MB],
 // copied to LDS before the stream starts (one short wait at the head of the kernel).
 // MB = blocks of 16 rows of X handled by every wavefront (M <= 16 * MB).  MB > 1 extends the stream to
 // M <= 64: the weights are still read and unpacked once, X (L2-resident) is read MB times as much.
+// nb = the workgroup's block of 64 output channels, s = its K-slice.  gnb = the index under which the block meets
+// its other K-slices in the workspace: nb for a single layer; in a group of layers launched together, the block's
+// index in the concatenation of their channel blocks.
 template <int WAVES, int D, int DQ, bool FGQ, int FMT, int MB>
-__global__ __launch_bounds__(WAVES * 64) void decode_kernel(
+__device__ __forceinline__ void decode_block(
     const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
     const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
     float4v* __restrict__ partials, uint32_t* __restrict__ counters, unsigned long long* __restrict__ slots,
-    int split_k, int pairwise, int gshift)
+    int split_k, int pairwise, int gshift, int nb, int s, int gnb)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int ktiles = K / kTile;
-    const int nb = blockIdx.x / split_k, s = blockIdx.x % split_k;
     const int kt_per = ktiles / split_k;
     const int kt_end = (s + 1) * kt_per;
     static_assert(MB == 1 || !FGQ, "several row blocks: row-wise scales only");
@@ -212,7 +214,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
         // pairwise meeting, two values per slot: thread tid owns slots 2*tid and 2*tid + 1 of a node
         if (active[0]) {
             const size_t node = (size_t)32 * M;          // 64-bit slots per tree node
-            unsigned long long* mine = slots + (size_t)nb * split_k * node + tid * 2;
+            unsigned long long* mine = slots + (size_t)gnb * split_k * node + tid * 2;
             Pair p0{sum[0][0], sum[0][1]}, p1{sum[0][2], sum[0][3]};
             keep_lo = meet_tree(mine, node, s, split_k, p0);
             keep_hi = meet_tree(mine + 1, node, s, split_k, p1);
@@ -224,8 +226,8 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
 #pragma unroll
         for (int c = 0; c < MB; c++)
             if (active[c])
-                store_partial(partial_window(partials + ((size_t)nb * split_k + s) * (256 * MB), kSliceBytes), c * 256 + tid, sum[c]);
-        if (!arrive_last(&counters[nb * kCounterStride], (uint32_t)split_k)) return;
+                store_partial(partial_window(partials + ((size_t)gnb * split_k + s) * (256 * MB), kSliceBytes), c * 256 + tid, sum[c]);
+        if (!arrive_last(&counters[gnb * kCounterStride], (uint32_t)split_k)) return;
 #pragma unroll
         for (int c = 0; c < MB; c++) {
             if (!active[c]) continue;
@@ -237,7 +239,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
 #pragma unroll
                 for (int u = 0; u < G; u++) {
                     const int sl = min(ss + u, split_k - 1);
-                    v[u] = load_partial(partial_window(partials + ((size_t)nb * split_k + sl) * (256 * MB), kSliceBytes), c * 256 + tid);
+                    v[u] = load_partial(partial_window(partials + ((size_t)gnb * split_k + sl) * (256 * MB), kSliceBytes), c * 256 + tid);
                 }
 #pragma unroll
                 for (int u = 0; u < G; u++)
@@ -264,6 +266,66 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(
             *reinterpret_cast<half2v*>(dst + 2) = half2v{y[2], y[3]};
         }
     }
+}
+
+template <int WAVES, int D, int DQ, bool FGQ, int FMT, int MB>
+__global__ __launch_bounds__(WAVES * 64) void decode_kernel(
+    const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
+    const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
+    float4v* __restrict__ partials, uint32_t* __restrict__ counters, unsigned long long* __restrict__ slots,
+    int split_k, int pairwise, int gshift)
+{
+    const int nb = blockIdx.x / split_k, s = blockIdx.x % split_k;
+    decode_block<WAVES, D, DQ, FGQ, FMT, MB>(X, M, hi, lo, scales, N, K, Y, partials, counters, slots, split_k, pairwise,
+                                             gshift, nb, s, nb);
+}
+
+// ---- several layers in one launch
+// Layers that read activations of the same height M and are independent of one another (the q, k, v projections
+// of an attention block; the gate and up projections of a feed-forward block) can share one launch: the
+// workgroups of all of them start together, so the small layers ride in the shadow of the large one instead of
+// paying a launch each.  The launch treats the layers' channel blocks as one list (layer 0's blocks, then layer
+// 1's, ...) and gives every block the same plan; a workgroup finds its layer by comparing its position in that
+// list with the layers' first positions.
+constexpr int kGroupMax = FP6_GROUP_MAX;
+struct DecodeLayer {
+    const uint16_t* X;
+    const u32x4* hi;
+    const u32x4* lo;
+    const uint16_t* scales;
+    uint16_t* Y;
+    int N;
+};
+struct DecodeGroup {
+    DecodeLayer layer[kGroupMax];
+    int first_block[kGroupMax];       // index of the layer's first channel block in the list; INT_MAX for unused entries
+};
+
+// The layer of channel block `gnb`; the selects run on scalar registers (gnb is uniform in the workgroup).
+__device__ __forceinline__ DecodeLayer layer_of(const DecodeGroup& g, int gnb, int* first)
+{
+    DecodeLayer a = g.layer[0];
+    *first = 0;
+#pragma unroll
+    for (int i = 1; i < kGroupMax; i++) {
+        if (gnb >= g.first_block[i]) {
+            a = g.layer[i];
+            *first = g.first_block[i];
+        }
+    }
+    return a;
+}
+
+template <int WAVES, int D>
+__global__ __launch_bounds__(WAVES * 64) void decode_group_kernel(
+    DecodeGroup g, int M, int K, float4v* __restrict__ partials, uint32_t* __restrict__ counters,
+    unsigned long long* __restrict__ slots, int split_k, int pairwise)
+{
+    const int gnb = __builtin_amdgcn_readfirstlane(blockIdx.x / split_k), s = blockIdx.x % split_k;
+    int first;
+    const DecodeLayer a = layer_of(g, gnb, &first);
+    decode_block<WAVES, D, kBiasShift, false, kE3M2, 1>(a.X, M, a.hi, a.lo, a.scales, a.N, K, a.Y, partials, counters,
+                                                        slots, split_k, pairwise, -1, gnb - first, s, gnb);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -293,20 +355,16 @@ __device__ __forceinline__ HalfRaw load_half(const u32x4* __restrict__ hi, const
     return r;
 }
 
+// h = which half of the block's 64 channels; nb, s, gnb as in decode_block.
 template <int WAVES, int D, int FMT = kE3M2>
-__global__ __launch_bounds__(WAVES * 64) void decode_half_kernel(
+__device__ __forceinline__ void decode_half_block(
     const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
     const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
     float4v* __restrict__ partials, uint32_t* __restrict__ counters, unsigned long long* __restrict__ slots,
-    int split_k, int pairwise)
+    int split_k, int pairwise, int h, int nb, int s, int gnb)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int ktiles = K / kTile;
-    // ids b and b + 8 are the two halves of one (block, slice) unit
-    const int h = (blockIdx.x >> 3) & 1;
-    const int unit = (blockIdx.x & 7) + 8 * (blockIdx.x >> 4);
-    if (unit >= (N / kTile) * split_k) return;            // the grid is padded to a multiple of 16
-    const int nb = unit / split_k, s = unit % split_k;
     const int kt_per = ktiles / split_k;
     const int kt_end = (s + 1) * kt_per;
     const int m = lane & 15, g = lane >> 4;
@@ -381,7 +439,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_half_kernel(
     if (split_k > 1 && pairwise) {
         if (active) {
             const size_t node = (size_t)32 * M;          // the two halves share their block's tree nodes
-            unsigned long long* mine = slots + (size_t)nb * split_k * node + (h * 8 * M + tid) * 2;
+            unsigned long long* mine = slots + (size_t)gnb * split_k * node + (h * 8 * M + tid) * 2;
             Pair p0{sum[0], sum[1]}, p1{sum[2], sum[3]};
             keep_lo = meet_tree(mine, node, s, split_k, p0);
             keep_hi = meet_tree(mine + 1, node, s, split_k, p1);
@@ -389,8 +447,8 @@ __global__ __launch_bounds__(WAVES * 64) void decode_half_kernel(
         }
     } else if (split_k > 1) {
         if (active)
-            store_partial(partial_window(partials + ((size_t)nb * split_k + s) * 256, 4096), h * 128 + tid, sum);
-        if (!arrive_last(&counters[(nb * 2 + h) * kCounterStride], (uint32_t)split_k)) return;
+            store_partial(partial_window(partials + ((size_t)gnb * split_k + s) * 256, 4096), h * 128 + tid, sum);
+        if (!arrive_last(&counters[(gnb * 2 + h) * kCounterStride], (uint32_t)split_k)) return;
         if (active) {
             sum = float4v{0.f, 0.f, 0.f, 0.f};
             for (int ss = 0; ss < split_k; ss += 16) {
@@ -398,7 +456,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_half_kernel(
 #pragma unroll
                 for (int u = 0; u < 16; u++) {
                     const int sl = min(ss + u, split_k - 1);
-                    v[u] = load_partial(partial_window(partials + ((size_t)nb * split_k + sl) * 256, 4096), h * 128 + tid);
+                    v[u] = load_partial(partial_window(partials + ((size_t)gnb * split_k + sl) * 256, 4096), h * 128 + tid);
                 }
 #pragma unroll
                 for (int u = 0; u < 16; u++)
@@ -419,6 +477,37 @@ __global__ __launch_bounds__(WAVES * 64) void decode_half_kernel(
             *reinterpret_cast<half2v*>(dst + 2) = half2v{y[2], y[3]};
         }
     }
+}
+
+template <int WAVES, int D, int FMT = kE3M2>
+__global__ __launch_bounds__(WAVES * 64) void decode_half_kernel(
+    const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
+    const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
+    float4v* __restrict__ partials, uint32_t* __restrict__ counters, unsigned long long* __restrict__ slots,
+    int split_k, int pairwise)
+{
+    // ids b and b + 8 are the two halves of one (block, slice) unit
+    const int h = (blockIdx.x >> 3) & 1;
+    const int unit = (blockIdx.x & 7) + 8 * (blockIdx.x >> 4);
+    if (unit >= (N / kTile) * split_k) return;            // the grid is padded to a multiple of 16
+    const int nb = unit / split_k, s = unit % split_k;
+    decode_half_block<WAVES, D, FMT>(X, M, hi, lo, scales, N, K, Y, partials, counters, slots, split_k, pairwise, h, nb, s, nb);
+}
+
+// several layers in one launch (see decode_group_kernel); `units` = channel blocks of all layers x split_k
+template <int WAVES, int D>
+__global__ __launch_bounds__(WAVES * 64) void decode_half_group_kernel(
+    DecodeGroup g, int M, int K, int units, float4v* __restrict__ partials, uint32_t* __restrict__ counters,
+    unsigned long long* __restrict__ slots, int split_k, int pairwise)
+{
+    const int h = (blockIdx.x >> 3) & 1;
+    const int unit = (blockIdx.x & 7) + 8 * (blockIdx.x >> 4);
+    if (unit >= units) return;
+    const int gnb = __builtin_amdgcn_readfirstlane(unit / split_k), s = unit % split_k;
+    int first;
+    const DecodeLayer a = layer_of(g, gnb, &first);
+    decode_half_block<WAVES, D, kE3M2>(a.X, M, a.hi, a.lo, a.scales, a.N, K, a.Y, partials, counters, slots, split_k,
+                                       pairwise, h, gnb - first, s, gnb);
 }
 
 template <int WAVES, int D, int FMT = kE3M2>
@@ -480,6 +569,33 @@ hipError_t launch_decode(const LinearPlan& p, const uint16_t* X, int64_t M, cons
         case 84: return launch_decode_t<8, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
         default: return launch_decode_t<4, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     }
+}
+
+// One launch for `count` layers that share M and K (the plan `p` was made for their channel blocks taken together).
+hipError_t launch_decode_group(const LinearPlan& p, int count, const GroupLayer* layers, int64_t M, int64_t K, void* workspace,
+                               hipStream_t stream)
+{
+    uint32_t* counters = reinterpret_cast<uint32_t*>(workspace);
+    float4v* partials = reinterpret_cast<float4v*>(reinterpret_cast<char*>(workspace) + kZeroBytes);
+    unsigned long long* slots = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(workspace) + kCounterBytes);
+    DecodeGroup g;
+    int64_t blocks = 0;
+    for (int i = 0; i < kGroupMax; i++) {
+        const GroupLayer& l = layers[i < count ? i : 0];
+        g.layer[i] = DecodeLayer{l.X, (const u32x4*)l.hi, (const u32x4*)l.lo, l.scales, l.Y, (int)l.N};
+        g.first_block[i] = i < count ? (int)blocks : 0x7FFFFFFF;
+        if (i < count) blocks += l.N / kTile;
+    }
+    const int64_t units = blocks * p.split_k;
+    if (p.half_tiles) {
+        const unsigned grid = (unsigned)((units + 7) / 8 * 16);
+        hipLaunchKernelGGL((decode_half_group_kernel<4, 4>), dim3(grid), dim3(256), 0, stream, g, (int)M, (int)K, (int)units,
+                           partials, counters, slots, p.split_k, p.pairwise);
+    } else {
+        hipLaunchKernelGGL((decode_group_kernel<4, 4>), dim3((unsigned)units), dim3(256), 0, stream, g, (int)M, (int)K,
+                           partials, counters, slots, p.split_k, p.pairwise);
+    }
+    return hipGetLastError();
 }
 
 }  // namespace fp6

@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "../../include/fp6_linear.h"
+
 namespace fp6 {
 
 // Weight formats.  kE3M2: FP6, planes of 4 + 2 bits (Section 5.1).  kE3M1: FP5, the same
@@ -53,6 +55,18 @@ struct LinearPlan {
 // Heuristic (or caller-forced) plan; returns false if the request is invalid for the shape.
 // `block` = elements along K per scale (0 = row-wise).
 bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int variant, int split_k, LinearPlan* plan);
+
+// One layer of a group of layers launched together (fp6_linear_group).
+struct GroupLayer {
+    const uint16_t* X;
+    const void* hi;
+    const void* lo;
+    const uint16_t* scales;
+    uint16_t* Y;
+    int64_t N;
+};
+hipError_t launch_decode_group(const LinearPlan& p, int count, const GroupLayer* layers, int64_t M, int64_t K, void* workspace,
+                               hipStream_t stream);
 
 hipError_t launch_decode(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
                          const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
