@@ -228,6 +228,8 @@ int fp6_linear_group(int64_t M, const fp6_linear_problem *problems, int count, v
  *                       FP6_HINT_DEPTH may be 4, 6 or 8
  *   FP6_HINT_WIDTH(b)   gemm family: 64-channel blocks (= wavefronts) per workgroup, 8 or 4 (row-wise FP6,
  *                       bias-shift unpack)
+ *   FP6_HINT_KWAYS(2)   gemm family, 128 x 256 blocks (FP6_HINT_BLOCK_M(128) | FP6_HINT_WIDTH(4)): eight wavefronts,
+ *                       two sets of four that take alternate k tiles and add their sums in LDS
  * An unsupported combination returns FP6_ERR_VARIANT.
  */
 #define FP6_HINT_WAVES(w) ((int)(w) << 8)
@@ -237,6 +239,7 @@ int fp6_linear_group(int64_t M, const fp6_linear_problem *problems, int count, v
 #define FP6_HINT_DEQUANT(x) ((int)(x) << 22)
 #define FP6_HINT_HALF(x) ((int)(x) << 24)
 #define FP6_HINT_WIDTH(b) ((int)(b) << 26)
+#define FP6_HINT_KWAYS(x) (((int)(x) == 2) << 30)
 size_t fp6_linear_variant_workspace_bytes(int64_t M, int64_t N, int64_t K, int variant, int split_k);
 int fp6_linear_variant(const uint16_t *X, int64_t M, const void *hi_plane, const void *lo_plane,
                        const uint16_t *scales, int64_t N, int64_t K, uint16_t *Y,

@@ -49,6 +49,10 @@ def FP6_HINT_WIDTH(b: int) -> int:
     return int(b) << 26
 
 
+def FP6_HINT_KWAYS(x: int) -> int:
+    return int(int(x) == 2) << 30
+
+
 EXPORTS = ["fp6_layout_version", "fp6_status_string", "fp6_packed_sizes", "fp6_quantize_pack",
            "fp6_unpack_codes", "fp6_dequantize", "fp6_linear_workspace_bytes", "fp6_linear",
            "fp6_linear_variant_workspace_bytes", "fp6_linear_variant", "fp6_quantize_pack_fgq",
@@ -233,7 +237,9 @@ def plan_text(plan: dict) -> str:
     if fam == "decode":
         return "decode%s rows%d split%d%s wg%d" % (" half" if plan["half_tiles"] else "", plan["block_m"], plan["split_k"],
                                                    meet, plan["workgroups"])
-    return "gemm %dx%d split%d%s wg%d" % (plan["block_m"], 64 * plan["width"], plan["split_k"], meet, plan["workgroups"])
+    kways = " k%d" % (plan["waves"] // plan["width"]) if plan["waves"] > plan["width"] else ""
+    return "gemm %dx%d%s split%d%s wg%d" % (plan["block_m"], 64 * plan["width"], kways, plan["split_k"], meet,
+                                            plan["workgroups"])
 
 
 def new_workspace(nbytes: int, device) -> Optional[torch.Tensor]:

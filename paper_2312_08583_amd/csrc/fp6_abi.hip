@@ -94,7 +94,7 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
     // tuning hints ride in the upper bits of `variant`; 0 = automatic
     const int hint_waves = (variant >> 8) & 0xF, hint_depth = (variant >> 12) & 0xF, hint_bm = ((variant >> 16) & 0xF) * 16,
               hint_meet = (variant >> 20) & 0x3, hint_dequant = (variant >> 22) & 0x3,
-              hint_half = (variant >> 24) & 0x3, hint_gbn = (variant >> 26) & 0xF;
+              hint_half = (variant >> 24) & 0x3, hint_gbn = (variant >> 26) & 0xF, hint_kw = (variant >> 30) & 0x1;
     const int variant_hints = variant >> 8;
     variant &= 0xFF;
     if (variant == FP6_VARIANT_AUTO) {
@@ -113,6 +113,7 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
     if (split_k < 0 || (split_k > 0 && ktiles % split_k != 0)) return false;
 
     LinearPlan p{};
+    p.kw = 1;
     p.variant = variant;
     p.dequant = hint_dequant;
     p.format = format;
@@ -126,6 +127,7 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
     // the ablations exist for the default kernel configurations only
     if (hint_dequant > 2 || (hint_dequant && (hint_waves || hint_depth))) return false;
     if (hint_half && variant != FP6_VARIANT_DECODE) return false;
+    if (hint_kw && variant != FP6_VARIANT_GEMM) return false;
     if (hint_gbn && (variant != FP6_VARIANT_GEMM || hint_dequant || hint_waves || (hint_gbn != 8 && hint_gbn != 4)))
         return false;
     // 64-channel blocks (= wavefronts) per workgroup of the tiled kernel.  Eight share the activations best;
@@ -224,7 +226,31 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
         if (best_cost == 0.0) return false;
         gbn = best_gbn;
         p.gbn = (int)gbn;
-        p.depth = gbn == 8 ? (p.block_m == 128 ? 3 : 4) : (p.block_m == 128 ? 2 : (p.block_m == 64 ? 3 : 4));
+        if (hint_kw) {
+            // two K-ways inside the workgroup: plain FP6, 128 x 256 blocks, an even number of k tiles per slice
+            if (!plain || gbn != 4 || p.block_m != 128 || (ktiles / p.split_k) % 2) return false;
+            p.kw = 2;
+        } else if (plain && !variant_hints && !split_k && p.block_m == 128 && p.split_k > 1 &&
+                   ((M + 127) / 128) * ((nblocks + 3) / 4) <= kMaxCounters) {
+            // Where the model splits K, two of the K-ways can stay inside a workgroup of 128 x 256 (eight wavefronts
+            // that add their sums in LDS): the same workgroups and the same work per compute unit, with half the partial
+            // sums travelling through the workspace.  Measured at M = 512: 8192 x 22016 in four slices 170 -> 153 us,
+            // 8192 x 8192 in two slices 70.6 -> 67.5 us; 22016 x 8192, which is not split, stays as it is.
+            const int64_t mblk = (M + 127) / 128, wgs4 = mblk * ((nblocks + 3) / 4) * p.split_k;
+            if (gbn == 8 && p.split_k % 2 == 0) {
+                gbn = 4;
+                p.split_k /= 2;
+                p.kw = 2;
+            } else if (gbn == 4 && wgs4 >= 512 && p.split_k % 2 == 0) {
+                p.split_k /= 2;
+                p.kw = 2;
+            } else if (gbn == 4 && wgs4 <= 256 && (ktiles / p.split_k) % 2 == 0) {
+                p.kw = 2;
+            }
+            p.gbn = (int)gbn;
+        }
+        p.depth = gbn == 8 || p.kw == 2 ? (p.block_m == 128 ? 3 : 4) : (p.block_m == 128 ? 2 : (p.block_m == 64 ? 3 : 4));
+        p.waves = (int)gbn * p.kw;
         tiles = ((M + p.block_m - 1) / p.block_m) * ((nblocks + gbn - 1) / gbn);
         regs_per_tile = (int64_t)(p.block_m / 16) * 4 * 64 * gbn;
     }

@@ -14,6 +14,10 @@ hipError_t launch_gemm(const LinearPlan& p, const uint16_t* X, int64_t M, const 
     // Four-wavefront workgroups are built so that two fit a compute unit (at most 256 registers per lane and
     // 80 KB of LDS: a ring of 4, 3 and 2 stages at 32, 64 and 128 rows), i.e. two wavefronts per SIMD as with
     // eight-wavefront workgroups; measured 4-10 % faster than deeper rings with one workgroup per unit.
+    // Two K-ways inside a workgroup of 128 x 256: eight wavefronts, a ring of two stages for the activations (two k
+    // tiles each) and three for the planes: 136 KB of LDS.
+    if (p.gbn == 4 && p.kw == 2)
+        return launch_gemm_t<128, 3, 1, kBiasShift, false, kE3M2, 4, 2, 2>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);
     if (p.gbn == 4) {
         switch (p.block_m) {
             case 32: return launch_gemm_t<32, 4, 1, kBiasShift, false, kE3M2, 4>(p, X, M, hi, lo, scales, N, K, Y, workspace, stream);

@@ -82,28 +82,47 @@ __device__ __forceinline__ void wait_vmcnt()
 // a wavefront's 64 channels (128 bytes per block) ride along with every stage of the DMA ring.
 // GBN = 64-wide blocks of output channels per workgroup: 8 (512 channels), or 4 for launches that would
 // otherwise have too few workgroups.
-template <int BM, int D, int WN, int DQ, bool FGQ, int FMT, int GBN>
-__global__ __launch_bounds__(GBN / WN * 64, GBN == 4 ? 2 : 1) void gemm_kernel(
+// KW = K-ways inside the workgroup.  KW = 2 doubles the wavefronts: the second set (kh = 1) works on the same
+// BM x (64 * GBN) block of Y one k tile further along, so a step covers two k tiles, and the two sets' sums are
+// added in LDS after the main loop.  It is what two workgroups of a two-way K-split would do, with the meeting moved
+// from the workspace into LDS: where K has to be split to fill the chip, half of the partial sums never leave the
+// compute unit.  The ring then has DX stages for the activations (two k tiles each; they come from L2) and D stages
+// for the planes (they come from HBM and need the longer lead).
+template <int BM, int D, int WN, int DQ, bool FGQ, int FMT, int GBN, int KW = 1, int DX = D>
+__global__ __launch_bounds__(GBN / WN * KW * 64, (GBN == 4 && KW == 1) ? 2 : 1) void gemm_kernel(
     const uint16_t* __restrict__ X, int M, const u32x4* __restrict__ hi, const u32x4* __restrict__ lo,
     const uint16_t* __restrict__ scales, int N, int K, uint16_t* __restrict__ Y,
     float4v* __restrict__ partials, uint32_t* __restrict__ counters, int split_k, int gshift)
 {
-    static_assert(!FGQ || (WN == 1 && BM <= 64), "fine-grained scales: two accumulators must fit the register file");
-    constexpr int WAVES = GBN / WN;
-    constexpr int THREADS = WAVES * 64;
+    static_assert(!FGQ || (WN == 1 && BM <= 64 && KW == 1), "fine-grained scales: two accumulators must fit the register file");
+    static_assert(KW == 1 || (KW == 2 && WN == 1), "K-ways inside the workgroup: one or two");
+    static_assert(DX >= 2 && DX <= D, "the activations never need a longer lead than the planes");
+    constexpr int NWAVES = GBN / WN;                    // wavefronts side by side along N
+    constexpr int WAVES = NWAVES * KW;
+    constexpr int OUT_THREADS = NWAVES * 64;            // threads that hold the block of Y after the main loop
     constexpr int MT = BM / 16;                         // 16-row blocks of X per workgroup
     constexpr int NT = 4 * WN;                          // 16-channel blocks per wavefront
-    constexpr int XG = BM / 8;                          // 8-row groups (1 KB of DMA each) per stage
-    constexpr int XL = XG >= WAVES ? XG / WAVES : 1;    // X groups moved per wavefront and k tile
-    constexpr int kLoads = XL + 3 * WN + (FGQ ? 1 : 0); // DMA instructions per wavefront and k tile
-    constexpr int kXBytes = BM * kTile * 2;
-    constexpr int kScaleOff = kXBytes + GBN * kWaveTileBytes;     // FGQ: 256 bytes per wavefront
-    constexpr int kStageBytes = kScaleOff + (FGQ ? WAVES * 256 : 0);
-    constexpr int kTileRegs = MT * NT * THREADS;        // float4 per output tile
-    __shared__ __align__(16) unsigned char smem[D * kStageBytes];
+    constexpr int XG = KW * BM / 8;                     // 8-row groups (1 KB of DMA each) per stage: BM / 8 per k tile
+    constexpr int XL = XG >= WAVES ? XG / WAVES : 1;    // X groups moved per wavefront and step
+    constexpr int kLoads = XL + 3 * WN + (FGQ ? 1 : 0); // DMA instructions per wavefront and step
+    constexpr int kXBytes = KW * BM * kTile * 2;
+    constexpr int kPlaneBytes = GBN * KW * kWaveTileBytes + (FGQ ? WAVES * 256 : 0);   // per stage of the plane ring
+    constexpr int kScaleOff = GBN * KW * kWaveTileBytes;          // FGQ: 256 bytes per wavefront, inside the plane stage
+    constexpr int kPlaneBase = DX * kXBytes;                      // the plane ring follows the activation ring
+    constexpr int kRingBytes = DX * kXBytes + D * kPlaneBytes;
+    constexpr int kTileRegs = MT * NT * OUT_THREADS;    // float4 per output tile
+    constexpr int kSumBytes = KW > 1 ? kTileRegs * 16 : 0;        // LDS for adding the two K-ways
+    constexpr int kSmemBytes = kRingBytes > kSumBytes ? kRingBytes : kSumBytes;
+    // loads that may still be in flight when a step starts: everything issued after the step's activations
+    // (the rest of that step's loads and DX - 2 whole steps) and after its planes (D - 2 whole steps)
+    constexpr int kInFlight = ((DX - 2) * kLoads + 3 * WN + (FGQ ? 1 : 0)) < ((D - 2) * kLoads)
+                                  ? ((DX - 2) * kLoads + 3 * WN + (FGQ ? 1 : 0)) : ((D - 2) * kLoads);
+    __shared__ __align__(16) unsigned char smem[kSmemBytes];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kh = KW > 1 ? wave / NWAVES : 0;          // which of the K-ways this wavefront works on
+    const int nw = KW > 1 ? wave % NWAVES : wave;       // its position along N
     const int ktiles = K / kTile, nblocks = N / kTile;
     const int mblk = (M + BM - 1) / BM;
     const int nblk = (nblocks + GBN - 1) / GBN;
@@ -123,34 +142,39 @@ __global__ __launch_bounds__(GBN / WN * 64, GBN == 4 ? 2 : 1) void gemm_kernel(
     const int kt_per = ktiles / split_k;
     const int kt_begin = s * kt_per, kt_end = kt_begin + kt_per;
     const int m0 = mb * BM;
-    const int nb0 = nbw * GBN + wave * WN;     // first block of output channels of this wavefront
+    const int nb0 = nbw * GBN + nw * WN;       // first block of output channels of this wavefront
     const int i = lane & 15, g = lane >> 4;
     const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
-    // X DMA: this wavefront moves the 8-row groups j = (wave*XL + p) % XG; lane l of a group
-    // fetches row 8j + l/8, chunk (l%8) ^ (l/8), and lands at chunk position l%8.
+    // X DMA: this wavefront moves the 8-row groups j = (wave*XL + p) % XG; group j belongs to k tile j / (BM/8)
+    // of the step and holds rows 8 * (j % (BM/8)) .. +7; lane l of a group fetches row l/8 of them, chunk
+    // (l%8) ^ (l/8), and lands at chunk position l%8.
     uint32_t xlane[XL], xlds[XL];
 #pragma unroll
     for (int p = 0; p < XL; p++) {
         const int j = (wave * XL + p) % XG;
-        int row = m0 + j * 8 + (lane >> 3);
+        int row = m0 + (j % (BM / 8)) * 8 + (lane >> 3);
         row = row < M ? row : M - 1;      // rows past M are computed on valid data and dropped
-        xlane[p] = (uint32_t)row * (uint32_t)K * 2u + (uint32_t)(((lane & 7) ^ (lane >> 3)) * 16);
+        xlane[p] = (uint32_t)row * (uint32_t)K * 2u + (uint32_t)(((lane & 7) ^ (lane >> 3)) * 16) +
+                   (uint32_t)((j / (BM / 8)) * kTile * 2);
         xlds[p] = j * 1024;
     }
     const uint32_t wlane = lane * 16;
-    const uint32_t wlds = kXBytes + wave * WN * kWaveTileBytes;
+    const uint32_t wlds = wave * WN * kWaveTileBytes;       // inside a stage of the plane ring
     // blocks of channels past N are computed on the last valid block and dropped
     size_t tile0[WN];
 #pragma unroll
     for (int c = 0; c < WN; c++) tile0[c] = (size_t)min(nb0 + c, nblocks - 1) * ktiles;
 
-    // kLoads DMA instructions per call, always
-    auto issue = [&](int kt, int stage) {
-        const uint32_t sb = smem_base + stage * kStageBytes;
-        const unsigned char* xb = reinterpret_cast<const unsigned char*>(X) + (size_t)kt * (kTile * 2);
+    // kLoads DMA instructions per call, always: the activations of the step that starts at k tile `ktx` into stage sx
+    // of their ring, this wavefront's planes of the step that starts at `ktw` into stage sw of theirs
+    auto issue = [&](int ktx, int sx, int ktw, int sw) {
+        const uint32_t xs = smem_base + sx * kXBytes;
+        const uint32_t sb = smem_base + kPlaneBase + sw * kPlaneBytes;
+        const unsigned char* xb = reinterpret_cast<const unsigned char*>(X) + (size_t)ktx * (kTile * 2);
 #pragma unroll
-        for (int p = 0; p < XL; p++) dma16(xb, xlane[p], sb + xlds[p]);
+        for (int p = 0; p < XL; p++) dma16(xb, xlane[p], xs + xlds[p]);
+        const int kt = ktw + kh;          // this wavefront's k tile of the step
 #pragma unroll
         for (int c = 0; c < WN; c++) {
             const unsigned char* hb = reinterpret_cast<const unsigned char*>(hi) + (tile0[c] + kt) * kHiTileBytes;
@@ -169,10 +193,11 @@ __global__ __launch_bounds__(GBN / WN * 64, GBN == 4 ? 2 : 1) void gemm_kernel(
             dma4(sp, (lane & 31) * 4, sb + kScaleOff + wave * 256);
         }
     };
+    const int kt_last = kt_end - KW;      // first k tile of the last step (steps past it re-fetch it and are dropped)
 
-    // operand reads: row r = 16a + i, chunk 4q + g, at position (4q + g) ^ (i & 7)
-    const int xoff0 = i * (kTile * 2) + ((g ^ (i & 7)) * 16);
-    const int xoff1 = i * (kTile * 2) + (((4 + g) ^ (i & 7)) * 16);
+    // operand reads: row r = 16a + i, chunk 4q + g, at position (4q + g) ^ (i & 7), in this wavefront's k tile of the stage
+    const int xoff0 = kh * (BM * kTile * 2) + i * (kTile * 2) + ((g ^ (i & 7)) * 16);
+    const int xoff1 = kh * (BM * kTile * 2) + i * (kTile * 2) + (((4 + g) ^ (i & 7)) * 16);
 
     float4v acc[MT][NT];
     float4v part[FGQ ? MT : 1][FGQ ? NT : 1];      // FGQ: product sums of the current block of K
@@ -184,18 +209,25 @@ __global__ __launch_bounds__(GBN / WN * 64, GBN == 4 ? 2 : 1) void gemm_kernel(
             if (FGQ) part[a][t] = float4v{0.f, 0.f, 0.f, 0.f};
         }
 
+    // prologue: the steps 0 .. D-2 of the planes; their activations only as far as the shorter ring reaches
+    // (a call always issues kLoads loads: a slot that is not due yet fetches what step 0 needs once more)
 #pragma unroll
-    for (int u = 0; u < D - 1; u++) issue(min(kt_begin + u, kt_end - 1), u);
+    for (int u = 0; u < D - 1; u++) {
+        const int ux = u < DX - 1 ? u : 0;
+        issue(min(kt_begin + ux * KW, kt_last), ux, min(kt_begin + u * KW, kt_last), u);
+    }
 
-    // One k tile.  Its DMA was issued D-1 steps ago; D-2 younger groups may stay in flight.  The
-    // stage number u is a compile-time constant (the loop below is unrolled by D), so every LDS
-    // address is a register plus an immediate - a ring indexed at run time measured 10-20% slower.
-    auto step = [&](int kt, int u) {
-        wait_vmcnt<(D - 2) * kLoads>();
-        __syncthreads();          // everyone's DMA landed; everyone is done with the stage refilled next
-        issue(min(kt + D - 1, kt_end - 1), (u + D - 1) % D);
-        const unsigned char* st = smem + u * kStageBytes;
-        const unsigned char* wt = st + wlds;
+    // One step (KW k tiles).  Its planes were issued D-1 steps ago, its activations DX-1 steps ago; kInFlight younger
+    // loads may stay in flight.  The stage numbers are compile-time constants (the loop below is unrolled over a
+    // whole period of both rings), so every LDS address is a register plus an immediate - a ring indexed at run
+    // time measured 10-20% slower.
+    auto step = [&](int kt, int ux, int uw) {
+        wait_vmcnt<kInFlight>();
+        __syncthreads();          // everyone's DMA landed; everyone is done with the stages refilled next
+        issue(min(kt + (DX - 1) * KW, kt_last), (ux + DX - 1) % DX, min(kt + (D - 1) * KW, kt_last), (uw + D - 1) % D);
+        const unsigned char* st = smem + ux * kXBytes;
+        const unsigned char* wt = smem + kPlaneBase + uw * kPlaneBytes + wlds;
+        const unsigned char* sct = smem + kPlaneBase + uw * kPlaneBytes + kScaleOff;
         TileRaw raw[WN];
 #pragma unroll
         for (int c = 0; c < WN; c++) {
@@ -236,7 +268,7 @@ __global__ __launch_bounds__(GBN / WN * 64, GBN == 4 ? 2 : 1) void gemm_kernel(
             if ((((kt + 1) >> gshift) << gshift) == kt + 1 || kt + 1 == kt_end) {
 #pragma unroll
                 for (int t = 0; t < NT; t++) {
-                    const half4 h = *reinterpret_cast<const half4*>(st + kScaleOff + wave * 256 + (t * 16 + g * 4) * 2);
+                    const half4 h = *reinterpret_cast<const half4*>(sct + wave * 256 + (t * 16 + g * 4) * 2);
 #pragma unroll
                     for (int a = 0; a < MT; a++) {
 #pragma unroll
@@ -255,7 +287,7 @@ __global__ __launch_bounds__(GBN / WN * 64, GBN == 4 ? 2 : 1) void gemm_kernel(
         // (tuned for the instruction mix of the FP6 bias-shift unpack; the other variants are left to the compiler,
         // whose schedule needs fewer registers - and so are four-wavefront workgroups of 64 and 128 rows, whose two
         // wavefronts on a SIMD come from different workgroups and do not leave a barrier together: 2 % faster unhinted)
-        if (!FGQ && FMT == kE3M2 && DQ != kHalfMul && (GBN == 8 || BM == 32)) {
+        if (!FGQ && FMT == kE3M2 && DQ != kHalfMul && (GBN * KW == 8 || BM == 32)) {
         __builtin_amdgcn_sched_group_barrier(0x100, 3 * WN + MT, 0);     // planes + operands of k block 0
         __builtin_amdgcn_sched_group_barrier(0x002, 15, 0);              // first fragment
 #pragma unroll
@@ -268,17 +300,36 @@ __global__ __launch_bounds__(GBN / WN * 64, GBN == 4 ? 2 : 1) void gemm_kernel(
 #endif
     };
 
+    constexpr int P = (D % DX == 0) ? D : D * DX;      // steps after which both rings are back at stage 0
     int kt = kt_begin;
-    for (; kt + D <= kt_end; kt += D) {      // steady state: branch-free trips of D tiles
+    for (; kt + P * KW <= kt_end; kt += P * KW) {      // steady state: branch-free trips of P steps
 #pragma unroll
-        for (int u = 0; u < D; u++) step(kt + u, u);
+        for (int u = 0; u < P; u++) step(kt + u * KW, u % DX, u % D);
     }
 #pragma unroll
-    for (int u = 0; u < D - 1; u++) {        // the last (kt_end - kt_begin) % D tiles
-        if (kt + u < kt_end) step(kt + u, u);
+    for (int u = 0; u < P - 1; u++) {        // the remaining steps
+        if (kt + u * KW < kt_end) step(kt + u * KW, u % DX, u % D);
     }
     wait_vmcnt<0>();     // the over-fetched ring slots must land before LDS is given back
     __syncthreads();
+
+    // ---- the two K-ways of the workgroup: the second set of wavefronts hands its sums over in LDS and is done
+    if (KW > 1) {
+        float4v* sums = reinterpret_cast<float4v*>(smem);
+        if (kh == 1) {
+#pragma unroll
+            for (int a = 0; a < MT; a++)
+#pragma unroll
+                for (int t = 0; t < NT; t++) sums[(a * NT + t) * OUT_THREADS + nw * 64 + lane] = acc[a][t];
+        }
+        __syncthreads();
+        if (kh == 0) {
+#pragma unroll
+            for (int a = 0; a < MT; a++)
+#pragma unroll
+                for (int t = 0; t < NT; t++) acc[a][t] += sums[(a * NT + t) * OUT_THREADS + nw * 64 + lane];
+        }
+    }
 
     // Everything below is addressed through a copy of the thread index that the compiler cannot
     // see through, so that none of its address arithmetic is hoisted above the main loop, where it
@@ -289,21 +340,28 @@ __global__ __launch_bounds__(GBN / WN * 64, GBN == 4 ? 2 : 1) void gemm_kernel(
     const int i2 = tid2 & 15, g2 = (tid2 >> 4) & 3;
 
     // ---- K-slices of other workgroups
+    const bool holds_y = KW == 1 || kh == 0;       // (wave-uniform) the wavefronts that hold the block of Y
     if (split_k > 1) {
         const int tile = nbw * mblk + mb, ntiles = mblk * nblk;
-        {
+        if (holds_y) {
             __amdgpu_buffer_rsrc_t win = partial_window(partials + ((size_t)s * ntiles + tile) * kTileRegs, kTileRegs * 16);
 #pragma unroll
             for (int a = 0; a < MT; a++)
 #pragma unroll
-                for (int t = 0; t < NT; t++) store_partial(win, (a * NT + t) * THREADS + tid2, acc[a][t]);
+                for (int t = 0; t < NT; t++) store_partial(win, (a * NT + t) * OUT_THREADS + tid2, acc[a][t]);
         }
         if (!arrive_last(&counters[tile * kCounterStride], (uint32_t)split_k)) return;
+        if (!holds_y) return;
+        // Two slices: the one that arrives last adds the other's sums to its own, which it still holds - a + b
+        // does not depend on who that is.  More slices: all of them are read back and added in slice order.
+        const bool two = split_k == 2;
+        if (!two) {
 #pragma unroll
-        for (int a = 0; a < MT; a++)
+            for (int a = 0; a < MT; a++)
 #pragma unroll
-            for (int t = 0; t < NT; t++) acc[a][t] = float4v{0.f, 0.f, 0.f, 0.f};
-        for (int ss = 0; ss < split_k; ss++) {
+                for (int t = 0; t < NT; t++) acc[a][t] = float4v{0.f, 0.f, 0.f, 0.f};
+        }
+        for (int ss = two ? 1 - s : 0; ss < (two ? 2 - s : split_k); ss++) {
             __amdgpu_buffer_rsrc_t win = partial_window(partials + ((size_t)ss * ntiles + tile) * kTileRegs, kTileRegs * 16);
             // sixteen 16-byte loads in flight at a time: more would need registers the main loop
             // cannot spare
@@ -314,7 +372,7 @@ __global__ __launch_bounds__(GBN / WN * 64, GBN == 4 ? 2 : 1) void gemm_kernel(
 #pragma unroll
                 for (int a = 0; a < AG; a++)
 #pragma unroll
-                    for (int t = 0; t < NT; t++) v[a][t] = load_partial(win, ((a0 + a) * NT + t) * THREADS + tid2);
+                    for (int t = 0; t < NT; t++) v[a][t] = load_partial(win, ((a0 + a) * NT + t) * OUT_THREADS + tid2);
 #pragma unroll
                 for (int a = 0; a < AG; a++)
 #pragma unroll
@@ -322,6 +380,8 @@ __global__ __launch_bounds__(GBN / WN * 64, GBN == 4 ? 2 : 1) void gemm_kernel(
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+    } else if (!holds_y) {
+        return;
     }
 
     // ---- epilogue: lane holds channels n = 16t + 4g + r of row m = 16a + i  (i2, g2 = i, g)
@@ -363,7 +423,7 @@ __global__ __launch_bounds__(GBN / WN * 64, GBN == 4 ? 2 : 1) void gemm_kernel(
     }
 }
 
-template <int BM, int D, int WN, int DQ = kBiasShift, bool FGQ = false, int FMT = kE3M2, int GBN = 8>
+template <int BM, int D, int WN, int DQ = kBiasShift, bool FGQ = false, int FMT = kE3M2, int GBN = 8, int KW = 1, int DX = D>
 static hipError_t launch_gemm_t(const LinearPlan& p, const uint16_t* X, int64_t M, const void* hi, const void* lo,
                                 const uint16_t* scales, int64_t N, int64_t K, uint16_t* Y, void* workspace,
                                 hipStream_t stream)
@@ -372,7 +432,7 @@ static hipError_t launch_gemm_t(const LinearPlan& p, const uint16_t* X, int64_t 
     float4v* partials = reinterpret_cast<float4v*>(reinterpret_cast<char*>(workspace) + kZeroBytes);
     const int64_t mblk = (M + BM - 1) / BM, nblk = (N / kTile + GBN - 1) / GBN;
     const unsigned grid = (unsigned)(mblk * ((nblk * p.split_k + 7) / 8 * 8));   // padded: see the id mapping
-    hipLaunchKernelGGL((gemm_kernel<BM, D, WN, DQ, FGQ, FMT, GBN>), dim3(grid), dim3(GBN / WN * 64), 0, stream, X, (int)M,
+    hipLaunchKernelGGL((gemm_kernel<BM, D, WN, DQ, FGQ, FMT, GBN, KW, DX>), dim3(grid), dim3(GBN / WN * KW * 64), 0, stream, X, (int)M,
                        (const u32x4*)hi, (const u32x4*)lo, scales, (int)N, (int)K, Y, partials, counters, p.split_k, p.gshift);
     return hipGetLastError();
 }

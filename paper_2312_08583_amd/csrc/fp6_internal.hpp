@@ -50,6 +50,7 @@ struct LinearPlan {
     int gbn;            // GEMM: 64-channel blocks (= wavefronts) per workgroup: 8 or 4
     int half_tiles;     // DECODE: workgroups own 32 channels (half a tile) instead of 64
     int pairwise;       // DECODE with split_k > 1: K-slices meet pairwise in the slot region (1) or at a counter (0)
+    int kw;             // GEMM: K-ways inside the workgroup (1, or 2 with gbn = 4 and block_m = 128)
 };
 
 // Heuristic (or caller-forced) plan; returns false if the request is invalid for the shape.

@@ -283,6 +283,43 @@ def test_tiled_kernel_workgroup_widths(width, M, bm, split):
     assert_y_close(Y, Yref, (width, M, bm, split))
 
 
+@pytest.mark.parametrize("M,N,K,split", [(100, 320, 1024, 1), (130, 256, 2048, 2), (300, 704, 1536, 4), (512, 1024, 768, 1),
+                                         (129, 64, 128, 1), (512, 512, 4096, 8)])
+def test_tiled_kernel_with_two_k_ways_inside_the_workgroup(M, N, K, split):
+    """Eight wavefronts on a 128 x 256 block: two sets that take alternate k tiles and add their sums in LDS."""
+    W = inputs.weight(N, K, seed=210 + M, sigma=0.02, outlier_frac=0.001, device=DEV)
+    X = inputs.activation(M, K, seed=211 + split, device=DEV)
+    hi, lo, sc = _quant(W)
+    variant = (P.FP6_VARIANT_GEMM | P.binding.FP6_HINT_BLOCK_M(128) | P.binding.FP6_HINT_WIDTH(4) |
+               P.binding.FP6_HINT_KWAYS(2))
+    plan = P.fp6_linear_plan(M, N, K, variant=variant, split_k=split)
+    assert (plan["waves"], plan["width"], plan["block_m"], plan["split_k"]) == (8, 4, 128, split)
+    ws = P.new_workspace(max(plan["workspace_bytes"], 16), DEV)
+    Y = P.fp6_linear_variant(X, hi, lo, sc, N, K, variant, split, workspace=ws)
+    Y2 = P.fp6_linear_variant(X, hi, lo, sc, N, K, variant, split, workspace=ws)
+    torch.cuda.synchronize()
+    _, _, Yref = oracle_reference(W, X)
+    assert_y_close(Y, Yref, "two K-ways, split %d" % split)
+    assert torch.equal(Y.view(torch.int16), Y2.view(torch.int16)), "not reproducible"
+    if plan["workspace_bytes"]:
+        assert not ws[:min(plan["workspace_bytes"], P.binding.FP6_WORKSPACE_ZERO_BYTES)].any()
+
+
+def test_two_k_ways_need_an_even_number_of_k_tiles_per_slice_and_the_128_by_256_block():
+    B = P.binding
+    kw = P.FP6_VARIANT_GEMM | B.FP6_HINT_KWAYS(2)
+    a = torch.zeros(64, dtype=torch.uint8, device=DEV)
+    L, st = B.lib(), torch.cuda.current_stream().cuda_stream
+    def rc(M, N, K, variant, split):
+        return L.fp6_linear_variant(a.data_ptr(), M, a.data_ptr(), a.data_ptr(), a.data_ptr(), N, K, a.data_ptr(), None, 0, st,
+                                    variant, split)
+    assert rc(128, 256, 192, kw | B.FP6_HINT_BLOCK_M(128) | B.FP6_HINT_WIDTH(4), 1) == -5       # three k tiles
+    assert rc(128, 256, 384, kw | B.FP6_HINT_BLOCK_M(128) | B.FP6_HINT_WIDTH(4), 2) == -5       # two slices of three
+    assert rc(128, 256, 512, kw | B.FP6_HINT_BLOCK_M(64) | B.FP6_HINT_WIDTH(4), 1) == -5
+    assert rc(128, 256, 512, kw | B.FP6_HINT_BLOCK_M(128) | B.FP6_HINT_WIDTH(8), 1) == -5
+    assert rc(8, 256, 512, P.FP6_VARIANT_DECODE | B.FP6_HINT_KWAYS(2), 1) == -5
+
+
 @pytest.mark.parametrize("M", [17, 24, 32, 33, 47, 48, 64])
 @pytest.mark.parametrize("split", [1, 2, 6])
 def test_decode_family_with_several_row_blocks(M, split):
