@@ -64,7 +64,8 @@ __device__ __forceinline__ void tile_mac(const TileRaw& r, const XFrag (&x)[MB],
 // FGQ: one scale per `64 << gshift` elements along K (Section 3, fine-grained quantization)
 // instead of one per row.  A tile lies inside one such block, so its product sums are
 // formed in a zeroed accumulator and multiplied by the block's scales while they are added
-// to the running sum - "after matrix multiplication, before the accumulation" (Section 5.2).
+// to the running sum: the scale meets the block's finished product sum before the blocks
+// accumulate (the fine-grained rule of Section 5.2).
 // The scales of the workgroup's 64 channels for its whole K-slice (128 bytes per block) are
 // copied to LDS before the stream starts (one short wait at the head of the kernel).
 // MB = blocks of 16 rows of X handled by every wavefront (M <= 16 * MB).  MB > 1 extends the stream to

@@ -78,7 +78,8 @@ __device__ __forceinline__ void wait_vmcnt()
 // FGQ: one scale per `64 << gshift` elements along K (Section 3, fine-grained quantization).
 // The product sums of the k tiles of one such block are formed in a second accumulator; at
 // the end of the block they are multiplied by the block's scales and added to the running
-// sum - "after matrix multiplication, before the accumulation" (Section 5.2).  The scales of
+// sum: the scale is applied to each block's finished product sum, and only then do the blocks
+// accumulate (the fine-grained rule of Section 5.2).  The scales of
 // a wavefront's 64 channels (128 bytes per block) ride along with every stage of the DMA ring.
 // GBN = 64-wide blocks of output channels per workgroup: 8 (512 channels), or 4 for launches that would
 // otherwise have too few workgroups.
