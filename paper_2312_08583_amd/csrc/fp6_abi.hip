@@ -22,6 +22,41 @@ static bool shape_ok(int64_t N, int64_t K)
            K <= (int64_t)1 << 30 && N * K <= (int64_t)1 << 40;
 }
 
+// ---- the planner's fitted constants, all in one place
+//
+// Times are microseconds, rates bytes per microsecond.  Every figure was fitted on one MI355X to a sweep of forced
+// plans (fp6_linear with FP6_HINT_* and a forced split_k, timed as replays of a captured graph); the sweep behind
+// each group is named with it.  tests/test_plan_pins.py pins what the planner chooses with them.
+struct PlanModel {
+    // -- streaming kernel, fewer than 256 channel blocks.  M <= 16: 17 shapes from 1024 x 1024 to 8192 x 28672 at
+    //    M = 1, every divisor of the k tiles up to 32, full and half tiles.  M = 24 ... 64: 21 shapes, same splits.
+    double launch;              // fixed cost of a launch
+    double stream16, stream64;  // what all workgroups together pull from HBM (up to 16 rows; two or four row blocks)
+    double wg_full, wg_half, wg_half_fp5;   // what one workgroup pulls: 64 channels; 32 channels; 32 channels of FP5
+    double wg_rows_exponent;    // more than 16 rows: a workgroup pulls wg_full x (16 / M)^this
+    double meet_pair;           // two slices meeting pairwise
+    double meet_base16, meet_slice16;       // counter meeting, up to 16 rows: base + per slice
+    double meet_base64, meet_slice64;       // more rows: (base + per slice) x M / 16
+    // -- streaming against tiled kernel (plain FP6): sizes measured at M = 32 and 64 on 4096 x 4096, 4096 x 11008,
+    //    5120 x 5120, 28672 x 8192
+    int64_t stream_to_32_weights;           // up to 32 rows the streaming kernel wins up to this many weights
+    int64_t stream_to_64_blocks, stream_to_64_weights;   // up to 64 rows: up to this many channel blocks and weights
+    // -- tiled kernel: every (rows per workgroup, width, split) on 12 shapes from 4096 x 4096 to 8192 x 28672 at
+    //    M = 32 ... 512; the model's choice is 1 % behind the sweep's best on average, 7 % at worst
+    double step[3];             // one k tile of an eight-wavefront workgroup with 32, 64, 128 rows
+    double narrow_step;         // a four-wavefront workgroup takes this fraction of it ...
+    double shared_unit;         // ... times this when two of them share a compute unit
+    double slice[3];            // adding up one more slice's partial sums, per 32 / 64 / 128 rows (eight wavefronts)
+    double round_fixed;         // set-up and epilogue of a workgroup
+    double split_fixed;         // storing partial sums and the counter round trip, once the layer is split
+    double hbm_tiled;           // HBM stream under the tiled kernel's access pattern
+};
+static constexpr PlanModel kModel = {
+    2.5, 6.2e6, 3.87e6, 35e3, 29e3, 22e3, 0.565, 1.3, 1.4, 0.03, 0.5, 0.093,
+    (int64_t)72 << 20, 64, (int64_t)1 << 27,
+    {0.77, 0.993, 1.417}, 0.57, 1.964, {0.528, 1.588, 4.681}, 2.774, 3.216, 4.529e6,
+};
+
 // Number of K-slices for the decode family where the cost model below does not apply: layers of 256 channel
 // blocks or more at up to 16 rows of X (measured on MI355X at M = 1: no split from 384 blocks on; below, two
 // slices, which meet pairwise - cheaper than any larger number), eight-wavefront workgroups, very short K.
@@ -65,14 +100,16 @@ static void plan_small_decode(int64_t M, int64_t nblocks, int64_t ktiles, int ti
             const int64_t wgs = nblocks * d * (half ? 2 : 1);
             const double rounds = (double)((wgs + 255) / 256);
             const bool rows16 = M <= 16;
-            const double stream = bytes / (rows16 ? 6.2e6 : 3.87e6);
-            // (FP5 half tiles fetch the 1-bit plane four bytes a lane: 22 GB/s separates 8192 x 8192, where they win, from 8192 x 22016, where they lose)
-            const double rate = rows16 ? (half ? (tile_bytes == 3072 ? 29e3 : 22e3) : 35e3) : 35e3 * pow(16.0 / (double)M, 0.565);
+            const PlanModel& c = kModel;
+            const double stream = bytes / (rows16 ? c.stream16 : c.stream64);
+            // (FP5 half tiles fetch the 1-bit plane four bytes a lane: their lower rate separates 8192 x 8192, where they win, from 8192 x 22016, where they lose)
+            const double rate = rows16 ? (half ? (tile_bytes == 3072 ? c.wg_half : c.wg_half_fp5) : c.wg_full)
+                                       : c.wg_full * pow(16.0 / (double)M, c.wg_rows_exponent);
             const double unit = rounds * (bytes / (double)wgs) / rate;
             const double meet = d == 1 ? 0.0
-                                : rows16 ? (d == 2 ? 1.3 : 1.4 + 0.03 * (double)d)
-                                         : (0.5 + 0.093 * (double)d) * (double)M / 16.0;
-            const double cost = 2.5 + (stream > unit ? stream : unit) + meet;
+                                : rows16 ? (d == 2 ? c.meet_pair : c.meet_base16 + c.meet_slice16 * (double)d)
+                                         : (c.meet_base64 + c.meet_slice64 * (double)d) * (double)M / 16.0;
+            const double cost = c.launch + (stream > unit ? stream : unit) + meet;
             if (cost < best - 1e-9) {
                 best = cost;
                 *split_out = (int)d;
@@ -104,8 +141,8 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
         // Up to 64 rows it stays ahead where there are at most 64 channel blocks, too few tiles for the tiled kernel
         // (M = 64: 15.4 against 16.2 us at 4096 x 4096, 23.3 against 27.0 at 4096 x 11008; behind from 5120 channels on).
         const bool plain_call = format == kE3M2 && !block && !(variant_hints);
-        const bool stream = M <= 16 || (M <= 32 && plain_call && N * K <= ((int64_t)72 << 20)) ||
-                            (M <= 64 && plain_call && nblocks <= 64 && N * K <= ((int64_t)1 << 27));
+        const bool stream = M <= 16 || (M <= 32 && plain_call && N * K <= kModel.stream_to_32_weights) ||
+                            (M <= 64 && plain_call && nblocks <= kModel.stream_to_64_blocks && N * K <= kModel.stream_to_64_weights);
         variant = stream ? FP6_VARIANT_DECODE : FP6_VARIANT_GEMM;
     }
     if (variant != FP6_VARIANT_DECODE && variant != FP6_VARIANT_GEMM) return false;
@@ -201,8 +238,10 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
             for (int bm = 32; bm <= (block ? 64 : 128); bm *= 2) {
                 if (hint_bm ? bm != hint_bm : (bm > 32 && bm / 2 >= M)) continue;
                 const int64_t mblk = (M + bm - 1) / bm, nblk = (nblocks + g - 1) / g, t = mblk * nblk;
-                const double step1 = (bm == 128 ? 1.417 : (bm == 64 ? 0.993 : 0.77)) * (g == 8 ? 1.0 : 0.57);
-                const double slice = (bm == 128 ? 4.681 : (bm == 64 ? 1.588 : 0.528)) * (double)g / 8.0;
+                const PlanModel& c = kModel;
+                const int bi = bm == 128 ? 2 : (bm == 64 ? 1 : 0);
+                const double step1 = c.step[bi] * (g == 8 ? 1.0 : c.narrow_step);
+                const double slice = c.slice[bi] * (double)g / 8.0;
                 const int64_t cap = g == 4 ? 2 : 1;          // four-wavefront workgroups: two per compute unit
                 for (int64_t d = 1; d <= ktiles && d <= 64; d++) {
                     if (ktiles % d || (split_k && d != split_k)) continue;
@@ -210,10 +249,10 @@ bool make_plan(int format, int64_t M, int64_t N, int64_t K, int64_t block, int v
                     const int64_t wgs = t * d, resident = wgs < 256 * cap ? wgs : 256 * cap;
                     const int64_t per_die = (nblk * d + 7) / 8 * mblk;
                     const int64_t rounds = (per_die + 32 * cap - 1) / (32 * cap);
-                    const double step = step1 * (cap == 2 && per_die > 32 ? 1.964 : 1.0);   // two sharing a unit
-                    const double hbm_step = 3072.0 * (double)g * (double)resident / (double)mblk / 4.529e6;
-                    const double cost = (double)rounds * ((double)(ktiles / d) * (step > hbm_step ? step : hbm_step) + 2.774 +
-                                                          (d > 1 ? 3.216 + (double)d * slice : 0.0));
+                    const double step = step1 * (cap == 2 && per_die > 32 ? c.shared_unit : 1.0);   // two sharing a unit
+                    const double hbm_step = 3072.0 * (double)g * (double)resident / (double)mblk / c.hbm_tiled;
+                    const double cost = (double)rounds * ((double)(ktiles / d) * (step > hbm_step ? step : hbm_step) + c.round_fixed +
+                                                          (d > 1 ? c.split_fixed + (double)d * slice : 0.0));
                     if (best_cost == 0.0 || cost < best_cost) {
                         best_cost = cost;
                         p.block_m = bm;

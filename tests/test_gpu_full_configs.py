@@ -2,7 +2,8 @@
 bench.py times (plain fp6_linear, automatic plan).  Configs 2-3 are checked on the full
 matrix; configs 4-5 and the paper's kernel-table shapes on sampled output channels (rows
 of W are quantized independently, so the oracle can do any subset of them one by one):
-scales and codes bit-exact on the sample, Y within 2e-3 on the sample for all M rows."""
+scales and codes bit-exact on the sample, Y within 2e-3 on the sample for all M rows.  The grouped
+launches of the config-5 layer (fp6_linear_group over q+k+v and gate+up) are checked the same way."""
 import numpy as np
 import pytest
 import torch
@@ -124,3 +125,32 @@ def test_paper_kernel_table_shapes_fgq_and_fp5_sampled(si, kind):
 @pytest.mark.parametrize("si", [1, 4, 6])        # k (1024x8192), gate (22016x8192), down (8192x22016)
 def test_cfg5_shapes_fgq_and_fp5_sampled(si, M, kind):
     _check_variant(kind, "cfg5_34b_stack", si, M, block=256)
+
+
+# ---- the grouped launches of the config-5 layer (q+k+v, gate+up), as the benchmark's grouped leg issues them
+
+@pytest.mark.parametrize("M", [1, 8, 512])
+@pytest.mark.parametrize("group", [(0, 1, 2), (4, 5)])
+def test_cfg5_grouped_launches_sampled(group, M, sample=128):
+    workload = "cfg5_34b_stack"
+    shapes = [inputs.WORKLOADS[workload]["shapes"][si][1:] for si in group]
+    K = shapes[0][1]
+    X = inputs.activation(M, K, seed=inputs.workload_seed(workload, 9000 + group[0]) + M, device=DEV)
+    _packed.clear()
+    layers, weights = [], []
+    for si, (N, _) in zip(group, shapes):
+        W = inputs.workload_weight(workload, si, layer=1, device=DEV)
+        hi, lo, sc = P.fp6_quantize_pack(W)
+        weights.append(W)
+        layers.append((X, hi, lo, sc, N, K))
+    ys = P.fp6_linear_group(layers)
+    torch.cuda.synchronize()
+    for si, (N, _), W, (_, hi, lo, sc, _, _), Y in zip(group, shapes, weights, layers, ys):
+        rng = np.random.default_rng(N * 13 + si)
+        rows = np.sort(rng.choice(N, size=sample, replace=False))
+        rows[0], rows[-1] = 0, N - 1
+        ridx = torch.from_numpy(rows).to(DEV)
+        codes_o, scales_o = O.quantize(to_np16(W[ridx]))
+        assert np.array_equal(P.fp6_unpack_codes(hi, lo, N, K)[ridx].cpu().numpy(), codes_o)
+        Yref = O.linear(to_np16(X), codes_o, scales_o)
+        assert_y_close(Y[:, ridx], Yref, (workload, "group", si, M))
