@@ -244,6 +244,21 @@ def main():
             ceilings["mfma_only_" + name] = {"TFLOP/s": round(flop / (ms * 1e-3) / 1e12, 1), "us_per_launch": round(ms * 1e3 / reps, 1),
                                              "what": "v_mfma_f32_16x16x32_f16 on register operands, %d workgroups x 4 wavefronts, "
                                                      "sustained" % wgs}
+        # (c) the same MFMAs with two integer vector instructions behind each, the mix of the tiled kernel's loop (the
+        # unpack issues through the port the MFMAs issue through), at that kernel's two wavefronts per SIMD and at
+        # full occupancy
+        for name, wgs_mix, iters_mix in (("two_waves_per_simd", 512, 8000), ("full_occupancy", 2048, 2000)):
+            sink = torch.zeros(wgs_mix * 256, dtype=torch.float32, device=dev)
+            flop = P.fp6_probe_mfma(wgs_mix, iters_mix, True, sink, valu_mix=True) * reps
+
+            def mix_pass():
+                for _ in range(reps):
+                    P.fp6_probe_mfma(wgs_mix, iters_mix, True, sink, valu_mix=True)
+            ms = time_passes(mix_pass, 10, warm_s=0.5)
+            ceilings["mfma_with_two_valu_each_" + name] = {
+                "TFLOP/s": round(flop / (ms * 1e-3) / 1e12, 1),
+                "what": "the MFMA-only kernel, random operands, with a v_perm_b32 and a v_xor_b32 behind every MFMA, "
+                        "%d workgroups x 4 wavefronts" % wgs_mix}
 
     def ceiling_us(M, N, K):
         """Time a launch cannot beat on this machine: the plain read kernel over the same packed bytes (which includes
@@ -594,6 +609,9 @@ def main():
             rf["measured_ceiling"] = (ceilings["plain_read_per_launch"]["GB/s"] if M <= 118 else
                                       ceilings["mfma_only_random_operands"]["TFLOP/s"])
             rf["frac_of_measured_ceiling"] = rf["achieved"] / rf["measured_ceiling"]
+            if M > 118:
+                rf["mfma_with_unpack_mix_ceiling"] = ceilings["mfma_with_two_valu_each_two_waves_per_simd"]["TFLOP/s"]
+                rf["frac_of_mfma_with_unpack_mix_ceiling"] = rf["achieved"] / rf["mfma_with_unpack_mix_ceiling"]
         if grouped is not None and ("M%d" % M) in grouped:
             rf["grouped_calls"] = dict(grouped["M%d" % M], calls_per_step=grouped["calls_per_step"])
         return rf

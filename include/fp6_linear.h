@@ -384,17 +384,20 @@ int fp6_linear_v2_bf16(const uint16_t *X, int64_t M, const void *hi_plane, const
  *     16 * workgroups bytes) receives one folded word per wavefront.  bytes / duration is the read
  *     rate a kernel that does nothing else reaches on this chip.
  *   fp6_probe_mfma: `workgroups` workgroups of 4 wavefronts; each wavefront issues 8 * iters
- *     v_mfma_f32_16x16x32_f16 (wide == 0) or v_mfma_f32_32x32x16_f16 (wide != 0) on 8 independent
- *     accumulators; 4 + 2 operand fragments held in registers, pseudo-random fp16 in (-1, 1) if
- *     random_operands != 0, else zeros.  `sink` (device, at least 1024 * workgroups bytes)
- *     receives one float per lane.  Work of a launch: workgroups * 4 * 8 * iters * 16384 flop,
- *     twice that if wide.
+ *     MFMAs on 8 independent accumulators; 4 + 2 operand fragments held in registers,
+ *     pseudo-random fp16 in (-1, 1) if random_operands != 0, else zeros.  `form`:
+ *     0 = v_mfma_f32_16x16x32_f16; 1 = v_mfma_f32_32x32x16_f16; 2 = form 0 with two independent
+ *     integer vector instructions behind every MFMA (the instruction mix of the tiled kernel's
+ *     loop, whose unpack shares the vector issue port with the MFMAs).  `sink` (device, at least
+ *     1024 * workgroups bytes) receives one float per lane.  Work of a launch:
+ *     workgroups * 4 * 8 * iters * 16384 flop, twice that for form 1.
  * Errors: FP6_ERR_NULL, FP6_ERR_ALIGN, FP6_ERR_SHAPE (sizes out of range: workgroups 1 .. 2^20,
- * iters 1 .. 2^24, bytes >= 16), FP6_ERR_WORKSPACE (sink too small), FP6_ERR_HIP.
+ * iters 1 .. 2^24, bytes >= 16), FP6_ERR_VARIANT (form), FP6_ERR_WORKSPACE (sink too small),
+ * FP6_ERR_HIP.
  */
 int fp6_probe_read(const void *buf, size_t bytes, int workgroups, void *sink, size_t sink_bytes,
                    void *stream);
-int fp6_probe_mfma(int workgroups, int iters, int random_operands, int wide, void *sink,
+int fp6_probe_mfma(int workgroups, int iters, int random_operands, int form, void *sink,
                    size_t sink_bytes, void *stream);
 
 #ifdef __cplusplus

@@ -521,10 +521,15 @@ def fp6_probe_read(buf: torch.Tensor, workgroups: int, sink: torch.Tensor) -> No
                                 sink.numel() * sink.element_size(), _stream()), "fp6_probe_read")
 
 
-def fp6_probe_mfma(workgroups: int, iters: int, random_operands: bool, sink: torch.Tensor, wide: bool = False) -> int:
-    """One launch of the MFMA-only kernel; returns the flop count of the launch."""
+def fp6_probe_mfma(workgroups: int, iters: int, random_operands: bool, sink: torch.Tensor, wide: bool = False,
+                   valu_mix: bool = False) -> int:
+    """One launch of the MFMA-only kernel (valu_mix: with two integer vector instructions behind every MFMA);
+    returns the flop count of the launch."""
     if not (sink.is_cuda and sink.is_contiguous()):
         raise Fp6Error("sink must be a contiguous device tensor")
-    _check(lib().fp6_probe_mfma(workgroups, iters, int(bool(random_operands)), int(bool(wide)), sink.data_ptr(),
+    if wide and valu_mix:
+        raise Fp6Error("the instruction mix exists for the 16x16x32 MFMA only")
+    form = 2 if valu_mix else (1 if wide else 0)
+    _check(lib().fp6_probe_mfma(workgroups, iters, int(bool(random_operands)), form, sink.data_ptr(),
                                 sink.numel() * sink.element_size(), _stream()), "fp6_probe_mfma")
     return workgroups * 4 * 8 * iters * 16384 * (2 if wide else 1)

@@ -450,6 +450,14 @@ def test_probe_kernels_run_and_reject_bad_arguments():
     assert (out == 0).all()                   # zero operands
     with pytest.raises(P.Fp6Error):
         P.fp6_probe_mfma(5, 3, False, out)
+    # the form with integer instructions between the MFMAs does the same MFMAs: same sums, plus a parity bit
+    plain = torch.empty_like(out)
+    P.fp6_probe_mfma(4, 3, True, plain)
+    assert P.fp6_probe_mfma(4, 3, True, out, valu_mix=True) == flop
+    torch.cuda.synchronize()
+    extra = (out.double() - plain.double()).abs()
+    tol = 1e-5 * (1 + plain.abs().max().item())          # the bit is added in fp32
+    assert ((extra <= tol) | ((extra - 1).abs() <= tol)).all() and torch.isfinite(out).all()
 
 
 @pytest.mark.parametrize("seed", range(4))
