@@ -480,3 +480,25 @@ def test_automatic_plans_on_random_shapes(seed):
         torch.cuda.synchronize()
         assert np.array_equal(to_np16(sc[ridx]), scales_o), (M, N, K)
         assert_y_close(Y[:, ridx], O.linear(to_np16(X), codes_o, scales_o), (M, N, K))
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_automatic_plans_on_random_prefill_shapes(seed):
+    """The same for prefill sizes: 65 <= M < 700 rows, N up to 12.7 K and K up to 16.6 K, uniform, eight per seed -
+    the region of the 128-row blocks, with and without a K-split or two K-ways inside the workgroup."""
+    rng = np.random.default_rng(4700 + seed)
+    for i in range(8):
+        N = 64 * int(rng.integers(16, 200))
+        K = 64 * int(rng.integers(16, 260))
+        M = int(rng.integers(65, 700))
+        W = inputs.weight(N, K, seed=4800 + 10 * seed + i, sigma=0.02, outlier_frac=0.001, device=DEV)
+        X = inputs.activation(M, K, seed=4900 + 10 * seed + i, device=DEV)
+        rows = np.unique(np.concatenate([[0, N - 1], rng.choice(N, size=24, replace=False)]))
+        ridx = torch.from_numpy(rows).to(DEV)
+        codes_o, scales_o = O.quantize(to_np16(W[ridx]))
+        hi, lo, sc = _quant(W)
+        Y = P.fp6_linear(X, hi, lo, sc, N, K)
+        torch.cuda.synchronize()
+        text = P.plan_text(P.fp6_linear_plan(M, N, K))
+        assert np.array_equal(to_np16(sc[ridx]), scales_o), (M, N, K, text)
+        assert_y_close(Y[:, ridx], O.linear(to_np16(X), codes_o, scales_o), (M, N, K, text))
