@@ -146,6 +146,9 @@ size_t fp6_linear_workspace_bytes(int64_t M, int64_t N, int64_t K);
  *   hi_plane, lo_plane, scales  in  device, as written by fp6_quantize_pack
  *   Y         out device, fp16 bits [M,N] row-major
  *   workspace     device, >= fp6_linear_workspace_bytes(M,N,K) bytes (may be NULL if that is 0)
+ * Nothing is clamped and nothing is checked for finiteness: a result beyond the fp16 range is
+ * stored as an infinity, an infinite or NaN activation propagates through its row of Y by the
+ * rules of IEEE arithmetic (inf * 0 and inf - inf give NaN), other rows are not affected.
  */
 int fp6_linear(const uint16_t *X, int64_t M, const void *hi_plane, const void *lo_plane,
                const uint16_t *scales, int64_t N, int64_t K, uint16_t *Y,

@@ -425,6 +425,44 @@ def test_zero_activations_give_zeros_and_results_do_not_depend_on_stale_output()
     assert torch.count_nonzero(out).item() == 0          # every element written, none left NaN
 
 
+@pytest.mark.parametrize("variant,split", [(1, 1), (1, 2), (1, 4), (2, 1), (2, 2)])
+def test_overflow_and_non_finite_activations_propagate_as_in_the_oracle(variant, split):
+    """Nothing is clamped or detected: results beyond the fp16 range become infinities of the right sign, an infinite
+    activation gives +-inf (NaN where it meets a zero weight or an opposite infinity), a NaN poisons its row, and the
+    other rows are untouched - through the streaming and the tiled kernel, with and without a K-split (two slices of
+    the streaming kernel meet pairwise, four at a counter)."""
+    N, K, M = 256, 512, 6
+    W = inputs.weight(N, K, seed=5100, sigma=0.05, outlier_frac=0.001, device=DEV)
+    X = inputs.activation(M, K, seed=5101, device=DEV)
+    X[1, :] = 60000.0
+    X[2, 5] = float("inf")
+    X[3, 7] = float("nan")
+    X[4, 300] = float("-inf")
+    X[4, 301] = float("inf")
+    hi, lo, sc = _quant(W)
+    codes_o, scales_o = O.quantize(to_np16(W))
+    with np.errstate(all="ignore"):
+        Yref = O.linear(to_np16(X), codes_o, scales_o)
+    Y = P.fp6_linear_variant(X, hi, lo, sc, N, K, variant, split)
+    torch.cuda.synchronize()
+    y = Y.cpu().to(torch.float64).numpy()
+    # the oracle's result is not rounded to fp16: what lies beyond the largest fp16 number (65504; ties at 65520) must
+    # come out infinite, what lies well inside must not; the narrow band between is left to either
+    with np.errstate(invalid="ignore"):
+        big, inside = np.abs(Yref) > 65600, np.abs(Yref) < 65400
+    decided = big | inside | np.isnan(Yref)
+    assert (big[1] & np.isfinite(Yref[1])).any() and inside[1].any(), "row 1 should straddle the fp16 range"
+    assert np.isnan(Yref[3]).all() and not np.isfinite(Yref[2]).any()
+    assert np.array_equal(np.isnan(y), np.isnan(Yref))
+    assert np.array_equal(np.isposinf(y) & decided, big & (Yref > 0))
+    assert np.array_equal(np.isneginf(y) & decided, big & (Yref < 0))
+    assert_y_close(Y[[0, 5]], Yref[[0, 5]], (variant, split))
+    # the finite part of the overflowing row: 2e-3 of the value plus one fp16 step at that size
+    fin = inside[1]
+    err = np.abs(y[1][fin] - Yref[1][fin])
+    assert np.isfinite(y[1][fin]).all() and (err <= 2e-3 * np.abs(Yref[1][fin]) + 32.0).all()
+
+
 def test_probe_kernels_run_and_reject_bad_arguments():
     """The measurement aids launch, write their sinks, and refuse sinks that are too small."""
     buf = torch.arange(1 << 20, dtype=torch.int32, device=DEV)
